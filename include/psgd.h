@@ -1,0 +1,158 @@
+/*
+ * psgd.h - C boundary of the MI355X (gfx950) model-averaging library for decentralized
+ * parallel SGD.
+ *
+ * One iteration of (A)D-PSGD updates all learners at once as
+ *         W_{k+1} = W_k * T - alpha * g(Phi_k, xi_k)                       (Sec. 2, Eq. 2)
+ * with W the d x L matrix of learner weights (one column per learner), T an L x L doubly
+ * stochastic mixing matrix and g the matrix of per-learner gradients.  This library keeps
+ * one learner per ROW: X = W^T is a row-major [n, d] fp32 array (n = L learners, d
+ * parameters each) resident in one GPU's HBM, and the same update reads
+ *         X_out[i, :] = sum_s w[i, s] * X[nbr[i, s], :]  -  lr * G[i, :].
+ * Row i of the (nbr, w) table lists column i of T: the learners whose models feed
+ * learner i, and with what weight.  For the ring topologies of Sec. 3 every row has three
+ * slots in the order (self, left neighbour, right neighbour).
+ *
+ * Conventions for every call:
+ *   - plain C types only; "host" / "device" is stated per pointer; the caller owns every
+ *     buffer it passes and the library neither frees nor keeps it after the work that was
+ *     enqueued by the call has run;
+ *   - functions returning int give PSGD_OK (0) or a negative psgd_status; the text of the
+ *     last failure on the calling thread is available from psgd_last_error();
+ *   - nothing aborts or throws; the library uses the device that is current on the calling
+ *     thread (hipSetDevice / torch.cuda.set_device);
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls that take
+ *     a stream only enqueue work and return.
+ */
+#ifndef PSGD_H
+#define PSGD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Mixing topologies (Sec. 3). */
+enum {
+    PSGD_TOPO_RING = 0,      /* fixed ring T_0: weights 1/3 on self and both cyclic neighbours (Eq. 3) */
+    PSGD_TOPO_RAND_RING = 1  /* T_tau = P^T T_0 P with a fresh seeded permutation per step (Eq. 8)     */
+};
+
+enum { PSGD_DEG = 3 };       /* slots per table row: self, left, right */
+enum { PSGD_MAX_N = 512 };   /* largest learner count the kernels stage in LDS */
+
+typedef enum {
+    PSGD_OK = 0,
+    PSGD_EINVAL = -1,  /* null pointer, n or d out of range, unknown topology / delay_mode */
+    PSGD_EALIAS = -2,  /* buffers overlap in a way the requested mode cannot honour */
+    PSGD_EALIGN = -3,  /* a pointer is not aligned to its element size */
+    PSGD_EHIP = -4     /* a HIP runtime call failed (no device, launch error, ...) */
+} psgd_status;
+
+/*
+ * psgd_build_mixing - neighbour and weight table of one iteration's mixing matrix.
+ *
+ * Fixed ring (Sec. 3, Eq. 3): nbr[i] = (i, i-1 mod n, i+1 mod n).  Randomized ring (Sec. 3,
+ * Eq. 8; Sec. 4, RAND-PSGD: all learners draw the same permutation from a shared seed): a
+ * permutation sigma of 0..n-1 puts learner sigma[p] at ring position p, and learner i at
+ * position p gets nbr[i] = (i, sigma[p-1 mod n], sigma[p+1 mod n]).  All weights are
+ * (float)1/3.  For n = 1 and n = 2 the slots repeat and their shares add.
+ *
+ * The permutation is a pure function of (n, seed, step): a SplitMix64 stream whose state
+ * starts at seed XOR ((step + 1) * 0x9E3779B97F4A7C15 mod 2^64) drives a Durstenfeld shuffle
+ * (i = n-1 .. 1, j = high 64 bits of draw * (i + 1), swap sigma[i], sigma[j]).
+ * `seed` and `step` are ignored for PSGD_TOPO_RING.
+ *
+ *   nbr  host, int32 [n * 3], written        w  host, float [n * 3], written
+ * Host only; touches no device.  Errors: PSGD_EINVAL (null pointer, n < 1 or
+ * n > PSGD_MAX_N, unknown topology).
+ */
+int psgd_build_mixing(int topology, int n, uint64_t seed, uint64_t step,
+                      int32_t* nbr, float* w);
+
+/*
+ * psgd_mix_step - fused model averaging and SGD step (Sec. 2, Eq. 2), gradients in fp32.
+ *
+ *   X      device, float [n * d] row-major, read
+ *   X_out  device, float [n * d] row-major, written
+ *   G      device, float [n * d] row-major, read
+ *   nbr    device, int32 [n * 3]; w  device, float [n * 3]  (a table as built above, or any
+ *          table whose entries lie in [0, n); they are read by the kernel when it runs)
+ *   n      learners, 1 .. PSGD_MAX_N;   d  parameters per learner, >= 0 (0 is a no-op)
+ *   lr     learning rate alpha
+ *   delay_mode  0: G was computed from this X (D-PSGD, RAND-PSGD).  X_out may be the same
+ *                  buffer as X (mixing in place).
+ *               1: delay-by-one (Sec. 4, Eq. 14): G was computed from the previous iterate
+ *                  while this X was being produced; X stays read-only for the gradient
+ *                  producer that runs beside this step, so X_out must not be X.
+ *          The arithmetic is the same in both modes.
+ *
+ * Per element, in fp32 and in this order: acc = w0 * x_self; acc = fma(w1, x_left, acc);
+ * acc = fma(w2, x_right, acc); out = fma(-lr, g, acc).
+ *
+ * Enqueues one kernel on `stream`; returns without waiting.  Errors: PSGD_EINVAL;
+ * PSGD_EALIAS (X_out partially overlaps X, X_out overlaps G, or X_out == X with
+ * delay_mode 1); PSGD_EALIGN (X, X_out, G not 4-byte aligned); PSGD_EHIP.  A table entry
+ * outside [0, n) cannot be seen by the host: the kernel then writes nothing and raises the
+ * flag that psgd_device_status() reports.
+ */
+int psgd_mix_step(const float* X, float* X_out, const float* G,
+                  const int32_t* nbr, const float* w,
+                  int n, int64_t d, float lr, int delay_mode, void* stream);
+
+/*
+ * psgd_mix_step_bf16g - the same step with gradients stored as bfloat16 bit patterns
+ * (device, uint16 [n * d], 2-byte aligned).  Each gradient is widened exactly to fp32
+ * (bits << 16) inside the kernel; everything else is as in psgd_mix_step.
+ */
+int psgd_mix_step_bf16g(const float* X, float* X_out, const uint16_t* G_bf16,
+                        const int32_t* nbr, const float* w,
+                        int n, int64_t d, float lr, int delay_mode, void* stream);
+
+/*
+ * psgd_consensus_dist - sum_i || x_i - xbar ||^2 with xbar the mean of the n rows of X:
+ * the distance from consensus whose decay Sec. 3 (Eqs. 5, 11, 12) bounds.
+ *
+ *   X  device, float [n * d] row-major, read.
+ * Synchronous: waits for all work on the device, runs, waits again, returns the value.
+ * Differences are taken against row 0 and accumulated in fp64; partial sums are combined
+ * in a fixed order, so the result is bit-reproducible.  Returns NaN on error (see
+ * psgd_last_error()).  d = 0 or n = 1 gives 0.
+ */
+double psgd_consensus_dist(const float* X, int n, int64_t d);
+
+/*
+ * psgd_consensus_dist_async - the same value written to out_dev (device, double[1],
+ * 8-byte aligned) by work enqueued on `stream`.  Uses a per-device scratch buffer that the
+ * library allocates on first use: calls that may run concurrently on one device (two
+ * streams) race on it and must be serialised by the caller.
+ */
+int psgd_consensus_dist_async(const float* X, int n, int64_t d, double* out_dev, void* stream);
+
+/*
+ * psgd_synth_grad - synthetic stand-in for back-propagation in the delay-by-one workload:
+ * G[e] = fma(c, X_prev[e], noise[e]) over `count` fp32 elements (all device pointers,
+ * 4-byte aligned; G must not overlap the inputs).  It plays the gradient producer that
+ * Sec. 4 runs concurrently with the averaging of the current iterate.  Enqueues on `stream`.
+ */
+int psgd_synth_grad(const float* X_prev, const float* noise, float* G,
+                    int64_t count, float c, void* stream);
+
+/*
+ * psgd_device_status - waits for the current device, then returns the sticky flag word that
+ * kernels raise (bit 0: a mixing table held an entry outside [0, n) and the step wrote
+ * nothing).  `clear` != 0 resets it.  Negative psgd_status on failure.
+ */
+int psgd_device_status(int clear);
+
+/* Text of the last error on the calling thread ("" if none).  Static storage. */
+const char* psgd_last_error(void);
+
+/* Library version, for the binding's load check. */
+int psgd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PSGD_H */

@@ -1,0 +1,638 @@
+// HIP kernels (gfx950 / CDNA4) and their launchers for the model-averaging step
+//     X_out[i,:] = sum_s w[i,s] * X[nbr[i,s],:] - lr * G[i,:]            (Sec. 2, Eq. 2)
+// and for the consensus distance sum_i ||x_i - xbar||^2 (Sec. 3).
+//
+// The step is bound by HBM traffic (about 7 flops against 10-12 bytes per element), so the
+// design goal is to touch every X, G and X_out byte exactly once:
+//   * the update is separable by column, so a lane owns a group of 4 adjacent columns
+//     (one 128-bit access per row) and sees all n rows of it;
+//   * when the table describes a single ring (every table of Sec. 3 does), the lane walks
+//     the ring in position order holding three consecutive rows in registers, so each
+//     neighbour read is a register move, not a memory access, and the update may run in
+//     place because a row is only written after its old value is in registers;
+//   * any other table goes through an [n x columns] tile in LDS, loaded completely before
+//     the first write, which gives the same two properties at the price of a barrier.
+// The 3-slot table is staged in LDS once per workgroup; workgroups are persistent and
+// stride over the column groups, so that cost is paid once per launch.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <mutex>
+
+#include "psgd.h"
+#include "psgd_internal.h"
+
+namespace psgd {
+namespace {
+
+constexpr int kThreads = 256;        // 4 wavefronts of 64 lanes
+constexpr int kTileBytes = 32 * 1024;  // LDS budget of the tiled path per workgroup
+constexpr int kUnroll = 8;           // rows whose loads are in flight together per lane
+constexpr int kMaxGrid = 4096;       // upper bound on persistent workgroups (scratch sizing)
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ int g_status_word = 0;
+
+// ---------------------------------------------------------------------------------------
+// Column-group value types: VEC = 4 (128-bit accesses) or 1 (any d, any 4-byte alignment).
+// ---------------------------------------------------------------------------------------
+template <int VEC> struct Cols;
+template <> struct Cols<4> { typedef f32x4 T; };
+template <> struct Cols<1> { typedef float T; };
+
+__device__ __forceinline__ f32x4 splat4(float v) { return (f32x4){v, v, v, v}; }
+
+__device__ __forceinline__ float vfma(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
+__device__ __forceinline__ f32x4 vfma(float a, f32x4 b, f32x4 c) {
+    return __builtin_elementwise_fma(splat4(a), b, c);
+}
+
+// X, G and X_out are each touched once per step: mark the accesses non-temporal so they
+// stream through the caches instead of displacing one another.
+__device__ __forceinline__ float ld_x(const float* p, Cols<1>) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ f32x4 ld_x(const float* p, Cols<4>) {
+    return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+}
+__device__ __forceinline__ void st_x(float* p, float v) { __builtin_nontemporal_store(v, p); }
+__device__ __forceinline__ void st_x(float* p, f32x4 v) {
+    __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(p));
+}
+__device__ __forceinline__ float ld_g(const float* p, Cols<1> c) { return ld_x(p, c); }
+__device__ __forceinline__ f32x4 ld_g(const float* p, Cols<4> c) { return ld_x(p, c); }
+// bfloat16 is the upper half of an fp32, so widening is a 16-bit shift and exact.
+__device__ __forceinline__ float ld_g(const uint16_t* p, Cols<1>) {
+    return __uint_as_float((uint32_t)__builtin_nontemporal_load(p) << 16);
+}
+__device__ __forceinline__ f32x4 ld_g(const uint16_t* p, Cols<4>) {
+    const u32x2 b = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+    return (f32x4){__uint_as_float(b.x << 16), __uint_as_float(b.x & 0xFFFF0000u),
+                   __uint_as_float(b.y << 16), __uint_as_float(b.y & 0xFFFF0000u)};
+}
+
+// One output group.  The operation order is part of the boundary's contract.
+template <typename V>
+__device__ __forceinline__ V mix_one(float w0, float w1, float w2, V self, V left, V right,
+                                     V g, float neg_lr) {
+    V acc = self * w0;
+    acc = vfma(w1, left, acc);
+    acc = vfma(w2, right, acc);
+    return vfma(neg_lr, g, acc);
+}
+
+// One ring position, packed so the walk fetches it with a single 128-bit LDS read.
+struct __attribute__((aligned(16))) RingEnt {
+    int row;
+    float w0, w1, w2;
+};
+
+// LDS carve-up (dynamic, sized by the launcher):
+//   RingEnt ring[n] | int nbr[3n] | float w[3n] | scratch (ranking arrays or the data tile)
+struct Lds {
+    RingEnt* ring;
+    int* nbr;
+    float* w;
+    char* scratch;
+};
+__host__ __device__ inline size_t lds_table_bytes(int n) {
+    return (size_t)n * sizeof(RingEnt) + (size_t)n * 3 * (sizeof(int) + sizeof(float));
+}
+__device__ __forceinline__ Lds carve(char* base, int n) {
+    Lds l;
+    l.ring = reinterpret_cast<RingEnt*>(base);
+    l.nbr = reinterpret_cast<int*>(base + (size_t)n * sizeof(RingEnt));
+    l.w = reinterpret_cast<float*>(l.nbr + 3 * n);
+    // n * 40 bytes of tables; keep the scratch 16-byte aligned
+    l.scratch = base + ((lds_table_bytes(n) + 15) & ~(size_t)15);
+    return l;
+}
+
+// Ring entries are the same for every lane; moving them to scalar registers keeps the row
+// offsets and weights out of the vector register file.
+__device__ __forceinline__ int ring_row(const RingEnt* e) { return __builtin_amdgcn_readfirstlane(e->row); }
+__device__ __forceinline__ RingEnt ring_ent(const RingEnt* e) {
+    RingEnt r;
+    r.row = __builtin_amdgcn_readfirstlane(e->row);
+    r.w0 = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(e->w0)));
+    r.w1 = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(e->w1)));
+    r.w2 = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(e->w2)));
+    return r;
+}
+
+enum TableKind { kTableBad = 0, kTableRing = 1, kTableGeneral = 2 };
+
+// Stage the table in LDS, check it, and decide whether it is a single ring.
+//
+// A ring here means: slot 0 of row i is i itself, and the left/right slots are mutually
+// consistent (the right neighbour's left is i and vice versa), which makes "right" a
+// bijection, and following it from learner 0 visits all n learners.  The last property is
+// decided by parallel list ranking (pointer doubling) toward learner 0's left neighbour;
+// the resulting distances are the ring positions, used to fill `ring` in walk order.
+__device__ int stage_table(const int32_t* __restrict__ nbr, const float* __restrict__ w, int n,
+                           const Lds& l) {
+    const int tid = threadIdx.x;
+    int ok = 1;
+    for (int e = tid; e < 3 * n; e += kThreads) {
+        const int v = nbr[e];
+        l.nbr[e] = v;
+        l.w[e] = w[e];
+        ok &= (unsigned)v < (unsigned)n;
+    }
+    if (!__syncthreads_and(ok)) return kTableBad;
+
+    int ring = 1;
+    for (int i = tid; i < n; i += kThreads) {
+        const int left = l.nbr[3 * i + 1], right = l.nbr[3 * i + 2];
+        ring &= (l.nbr[3 * i] == i) & (l.nbr[3 * right + 1] == i) & (l.nbr[3 * left + 2] == i);
+    }
+    if (!__syncthreads_and(ring)) return kTableGeneral;
+
+    int* nxt_a = reinterpret_cast<int*>(l.scratch);
+    int* dst_a = nxt_a + n;
+    int* nxt_b = dst_a + n;
+    int* dst_b = nxt_b + n;
+    const int tail = l.nbr[1];  // learner 0's left neighbour ends the list that starts at 0
+    for (int i = tid; i < n; i += kThreads) {
+        nxt_a[i] = (i == tail) ? i : l.nbr[3 * i + 2];
+        dst_a[i] = (i == tail) ? 0 : 1;
+    }
+    __syncthreads();
+    for (int span = 1; span < n; span <<= 1) {
+        for (int i = tid; i < n; i += kThreads) {
+            const int j = nxt_a[i];
+            nxt_b[i] = nxt_a[j];
+            dst_b[i] = dst_a[i] + dst_a[j];
+        }
+        __syncthreads();
+        int* t = nxt_a; nxt_a = nxt_b; nxt_b = t;
+        t = dst_a; dst_a = dst_b; dst_b = t;
+    }
+    int reached = 1;
+    for (int i = tid; i < n; i += kThreads) reached &= (nxt_a[i] == tail);
+    if (!__syncthreads_and(reached)) return kTableGeneral;
+    for (int i = tid; i < n; i += kThreads) {
+        const int pos = n - 1 - dst_a[i];
+        RingEnt e;
+        e.row = i;
+        e.w0 = l.w[3 * i];
+        e.w1 = l.w[3 * i + 1];
+        e.w2 = l.w[3 * i + 2];
+        l.ring[pos] = e;
+    }
+    __syncthreads();
+    return kTableRing;
+}
+
+// ---------------------------------------------------------------------------------------
+// Ring walk: one lane, one column group, all n rows, registers only.
+// Rows are visited in ring order p = 0..n-1.  `first` and `last` (positions 0 and n-1) stay
+// in registers for the wrap-around, so every X element is loaded exactly once and, when
+// X_out aliases X, always before the store that replaces it.
+// ---------------------------------------------------------------------------------------
+template <int VEC, typename GT>
+__device__ __forceinline__ void ring_walk(const float* xc, float* oc, const GT* __restrict__ gc,
+                                          const RingEnt* ring, int n, int64_t d, float neg_lr) {
+    typedef typename Cols<VEC>::T V;
+    const Cols<VEC> tag{};
+    const V first = ld_x(xc + (int64_t)ring_row(ring) * d, tag);
+    const V last = (n > 1) ? ld_x(xc + (int64_t)ring_row(ring + n - 1) * d, tag) : first;
+    V prev = last, cur = first;
+    int p = 0;
+    // Whole batches: positions p .. p+U-1, whose right neighbours p+1 .. p+U are all fresh
+    // loads (none of them is position n-1 or the wrap to position 0).
+    for (; p + kUnroll <= n - 2; p += kUnroll) {
+        RingEnt e[kUnroll];
+        V xs[kUnroll], gs[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            e[u] = ring_ent(ring + p + u);
+            xs[u] = ld_x(xc + (int64_t)ring_row(ring + p + u + 1) * d, tag);
+            gs[u] = ld_g(gc + (int64_t)e[u].row * d, tag);
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            st_x(oc + (int64_t)e[u].row * d, mix_one<V>(e[u].w0, e[u].w1, e[u].w2, cur, prev, xs[u], gs[u], neg_lr));
+            prev = cur;
+            cur = xs[u];
+        }
+    }
+    // Remainder (at most U + 1 positions), with the wrap-around served from registers.
+    while (p < n) {
+        RingEnt e[kUnroll];
+        V xs[kUnroll], gs[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int pp = p + u;
+            if (pp < n) {
+                e[u] = ring_ent(ring + pp);
+                gs[u] = ld_g(gc + (int64_t)e[u].row * d, tag);
+                if (pp + 1 <= n - 2) xs[u] = ld_x(xc + (int64_t)ring_row(ring + pp + 1) * d, tag);
+                else if (pp + 1 == n - 1) xs[u] = last;
+                else xs[u] = first;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            if (p + u < n) {
+                st_x(oc + (int64_t)e[u].row * d, mix_one<V>(e[u].w0, e[u].w1, e[u].w2, cur, prev, xs[u], gs[u], neg_lr));
+                prev = cur;
+                cur = xs[u];
+            }
+        }
+        p += kUnroll;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Tiled path for tables that are not a single ring.  The workgroup's 256 lanes form
+// (256 / lpr) row groups of lpr lanes; a tile is n rows by lpr column groups.
+// ---------------------------------------------------------------------------------------
+template <int VEC, typename GT>
+__device__ void tile_path(const float* X, float* Xout, const GT* __restrict__ G, const Lds& l,
+                          int n, int64_t d, int64_t ncg, float neg_lr, int lpr) {
+    typedef typename Cols<VEC>::T V;
+    const Cols<VEC> tag{};
+    V* tile = reinterpret_cast<V*>(l.scratch);
+    const int lane = threadIdx.x % lpr, rg = threadIdx.x / lpr, nrg = kThreads / lpr;
+    const int64_t ntiles = (ncg + lpr - 1) / lpr;
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const int64_t cg = t * lpr + lane;
+        const bool active = cg < ncg;
+        const int64_t col = cg * VEC;
+        if (active)
+            for (int r = rg; r < n; r += nrg) tile[r * lpr + lane] = ld_x(X + (int64_t)r * d + col, tag);
+        __syncthreads();
+        if (active)
+            for (int r = rg; r < n; r += nrg) {
+                const V self = tile[l.nbr[3 * r] * lpr + lane];
+                const V left = tile[l.nbr[3 * r + 1] * lpr + lane];
+                const V right = tile[l.nbr[3 * r + 2] * lpr + lane];
+                const V g = ld_g(G + (int64_t)r * d + col, tag);
+                st_x(Xout + (int64_t)r * d + col,
+                     mix_one<V>(l.w[3 * r], l.w[3 * r + 1], l.w[3 * r + 2], self, left, right, g, neg_lr));
+            }
+        __syncthreads();
+    }
+}
+
+template <int VEC, typename GT>
+__global__ __launch_bounds__(kThreads) void mix_step_kernel(const float* X, float* Xout,
+                                                            const GT* __restrict__ G,
+                                                            const int32_t* __restrict__ nbr,
+                                                            const float* __restrict__ w, int n, int64_t d,
+                                                            float neg_lr, int lpr) {
+    extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+    const Lds l = carve(lds_raw, n);
+    const int kind = stage_table(nbr, w, n, l);
+    if (kind == kTableBad) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&g_status_word, 1);
+        return;
+    }
+    const int64_t ncg = d / VEC;  // the launcher picks VEC = 1 unless 4 divides d
+    if (kind == kTableRing) {
+        const int64_t stride = (int64_t)gridDim.x * kThreads;
+        for (int64_t cg = (int64_t)blockIdx.x * kThreads + threadIdx.x; cg < ncg; cg += stride) {
+            const int64_t col = cg * VEC;
+            ring_walk<VEC, GT>(X + col, Xout + col, G + col, l.ring, n, d, neg_lr);
+        }
+    } else {
+        tile_path<VEC, GT>(X, Xout, G, l, n, d, ncg, neg_lr, lpr);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Consensus distance.  Per column: with pivot s = X[0, j],
+//   sum_i (x_i - xbar)^2 = sum_i (x_i - s)^2 - (sum_i (x_i - s))^2 / n,
+// one pass, differences and sums in fp64 (the difference of two fp32 values is exact in
+// fp64 unless their exponents are more than 29 apart, and because the pivot is one of the
+// points the subtraction cancels at most a factor n).
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    return v;
+}
+
+__device__ __forceinline__ double block_sum(double v, double* lds4) {
+    v = wave_sum(v);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if (lane == 0) lds4[wave] = v;
+    __syncthreads();
+    double r = 0.0;
+    if (threadIdx.x == 0) r = (lds4[0] + lds4[1]) + (lds4[2] + lds4[3]);
+    return r;  // valid in thread 0
+}
+
+template <int VEC>
+__device__ __forceinline__ void acc_diff(double* a, double* b, typename Cols<VEC>::T x, const double* s);
+template <>
+__device__ __forceinline__ void acc_diff<1>(double* a, double* b, float x, const double* s) {
+    const double df = (double)x - s[0];
+    a[0] += df;
+    b[0] = fma(df, df, b[0]);
+}
+template <>
+__device__ __forceinline__ void acc_diff<4>(double* a, double* b, f32x4 x, const double* s) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const double df = (double)x[k] - s[k];
+        a[k] += df;
+        b[k] = fma(df, df, b[k]);
+    }
+}
+__device__ __forceinline__ void pivot_of(float x, double* s) { s[0] = (double)x; }
+__device__ __forceinline__ void pivot_of(f32x4 x, double* s) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) s[k] = (double)x[k];
+}
+
+template <int VEC>
+__global__ __launch_bounds__(kThreads) void consensus_partial_kernel(const float* __restrict__ X, int n,
+                                                                     int64_t d, double* __restrict__ partials) {
+    typedef typename Cols<VEC>::T V;
+    const Cols<VEC> tag{};
+    __shared__ double lds4[4];
+    const int64_t ncg = d / VEC;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    const double inv_n = 1.0 / (double)n;
+    double total = 0.0;
+    for (int64_t cg = (int64_t)blockIdx.x * kThreads + threadIdx.x; cg < ncg; cg += stride) {
+        const float* xc = X + cg * VEC;
+        double s[VEC], a[VEC], b[VEC];
+        pivot_of(ld_x(xc, tag), s);
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) a[k] = b[k] = 0.0;
+        int r = 1;
+        for (; r + kUnroll <= n; r += kUnroll) {
+            V xs[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) xs[u] = ld_x(xc + (int64_t)(r + u) * d, tag);
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) acc_diff<VEC>(a, b, xs[u], s);
+        }
+        if (r < n) {
+            V xs[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u)
+                if (r + u < n) xs[u] = ld_x(xc + (int64_t)(r + u) * d, tag);
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u)
+                if (r + u < n) acc_diff<VEC>(a, b, xs[u], s);
+        }
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) total += b[k] - a[k] * a[k] * inv_n;
+    }
+    const double bs = block_sum(total, lds4);
+    if (threadIdx.x == 0) partials[blockIdx.x] = bs;
+}
+
+// Fixed-order sum of the per-workgroup partials: lane t adds entries t, t+256, ... and the
+// 256 lane sums go through the same shuffle/LDS tree, so the result does not depend on
+// scheduling.
+__global__ __launch_bounds__(kThreads) void consensus_final_kernel(const double* __restrict__ partials, int count,
+                                                                   double* __restrict__ out) {
+    __shared__ double lds4[4];
+    double v = 0.0;
+    for (int i = threadIdx.x; i < count; i += kThreads) v += partials[i];
+    const double bs = block_sum(v, lds4);
+    if (threadIdx.x == 0) out[0] = bs;
+}
+
+__global__ __launch_bounds__(kThreads) void synth_grad_kernel(const float* __restrict__ xp,
+                                                              const float* __restrict__ noise, float* __restrict__ g,
+                                                              int64_t count, float c, int vec4) {
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    const int64_t tid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (vec4) {
+        const int64_t groups = count / 4;
+        for (int64_t i = tid; i < groups; i += stride) {
+            const f32x4 x = ld_x(xp + 4 * i, Cols<4>{});
+            const f32x4 z = ld_x(noise + 4 * i, Cols<4>{});
+            st_x(g + 4 * i, vfma(c, x, z));
+        }
+        for (int64_t i = groups * 4 + tid; i < count; i += stride) g[i] = vfma(c, xp[i], noise[i]);
+    } else {
+        for (int64_t i = tid; i < count; i += stride) g[i] = vfma(c, xp[i], noise[i]);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Host helpers.
+// ---------------------------------------------------------------------------------------
+struct DeviceInfo {
+    int cus = 0;
+    double* scratch = nullptr;  // kMaxGrid partials + 1 result slot
+};
+constexpr int kMaxDevices = 64;
+DeviceInfo g_dev[kMaxDevices];
+std::mutex g_dev_mutex;
+
+int hip_fail(hipError_t e, const char* what) {
+    return fail(PSGD_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+// Looks up (and caches) the current device's compute-unit count.
+int device_info(DeviceInfo** out, bool want_scratch) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(PSGD_EHIP, "device index %d unsupported", dev);
+    std::lock_guard<std::mutex> lock(g_dev_mutex);
+    DeviceInfo& di = g_dev[dev];
+    if (di.cus == 0) {
+        int cus = 0;
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return hip_fail(e, "hipDeviceGetAttribute");
+        di.cus = cus > 0 ? cus : 1;
+    }
+    if (want_scratch && !di.scratch) {
+        e = hipMalloc(reinterpret_cast<void**>(&di.scratch), sizeof(double) * (kMaxGrid + 1));
+        if (e != hipSuccess) return hip_fail(e, "hipMalloc(scratch)");
+    }
+    *out = &di;
+    return PSGD_OK;
+}
+
+inline bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+inline bool overlaps(const void* a, size_t abytes, const void* b, size_t bbytes) {
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + bbytes && b0 < a0 + abytes;
+}
+
+inline int persistent_grid(const DeviceInfo& di, int64_t work_items, int per_cu) {
+    int64_t need = (work_items + kThreads - 1) / kThreads;
+    int64_t cap = (int64_t)di.cus * per_cu;
+    if (cap > kMaxGrid) cap = kMaxGrid;
+    int64_t g = need < cap ? need : cap;
+    return (int)(g < 1 ? 1 : g);
+}
+
+template <typename GT>
+int mix_step_impl(const char* name, const float* X, float* X_out, const GT* G, const int32_t* nbr, const float* w,
+                  int n, int64_t d, float lr, int delay_mode, void* stream) {
+    clear_error();
+    if (!X || !X_out || !G || !nbr || !w) return fail(PSGD_EINVAL, "%s: null pointer", name);
+    if (n < 1 || n > PSGD_MAX_N) return fail(PSGD_EINVAL, "%s: n=%d outside 1..%d", name, n, (int)PSGD_MAX_N);
+    if (d < 0) return fail(PSGD_EINVAL, "%s: d=%lld is negative", name, (long long)d);
+    if (delay_mode != 0 && delay_mode != 1) return fail(PSGD_EINVAL, "%s: delay_mode=%d", name, delay_mode);
+    if (!aligned_to(X, 4) || !aligned_to(X_out, 4) || !aligned_to(G, sizeof(GT)) || !aligned_to(nbr, 4) ||
+        !aligned_to(w, 4))
+        return fail(PSGD_EALIGN, "%s: pointer not aligned to its element size", name);
+    if (d > 0 && (int64_t)n > INT64_MAX / 4 / d) return fail(PSGD_EINVAL, "%s: n*d overflows", name);
+    const size_t xbytes = (size_t)n * (size_t)d * sizeof(float), gbytes = (size_t)n * (size_t)d * sizeof(GT);
+    if (static_cast<const void*>(X) == static_cast<const void*>(X_out)) {
+        if (delay_mode == 1)
+            return fail(PSGD_EALIAS, "%s: delay-by-one keeps X read-only, X_out must be another buffer", name);
+    } else if (overlaps(X, xbytes, X_out, xbytes)) {
+        return fail(PSGD_EALIAS, "%s: X_out partially overlaps X", name);
+    }
+    if (overlaps(G, gbytes, X_out, xbytes)) return fail(PSGD_EALIAS, "%s: X_out overlaps G", name);
+    if (d == 0) return PSGD_OK;
+
+    DeviceInfo* di = nullptr;
+    if (int rc = device_info(&di, false)) return rc;
+
+    // 128-bit path needs every row start 16-byte aligned (8-byte for bf16 gradients).
+    const bool vec4 = (d % 4 == 0) && aligned_to(X, 16) && aligned_to(X_out, 16) && aligned_to(G, 4 * sizeof(GT));
+    const int vec = vec4 ? 4 : 1;
+    // Tile shape of the fallback path: widest power-of-two lane count whose tile fits.
+    int lpr = 64;
+    while (lpr > 1 && (size_t)n * lpr * vec * sizeof(float) > (size_t)kTileBytes) lpr >>= 1;
+    size_t scratch_bytes = (size_t)n * lpr * vec * sizeof(float);
+    if (scratch_bytes < (size_t)n * 4 * sizeof(int)) scratch_bytes = (size_t)n * 4 * sizeof(int);
+    const size_t lds_bytes = ((lds_table_bytes(n) + 15) & ~(size_t)15) + scratch_bytes;
+    if (lds_bytes > 64 * 1024) return fail(PSGD_EINVAL, "%s: n=%d needs %zu bytes of LDS", name, n, lds_bytes);
+
+    const int grid = persistent_grid(*di, d / vec, 8);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (vec4)
+        hipLaunchKernelGGL((mix_step_kernel<4, GT>), dim3(grid), dim3(kThreads), lds_bytes, s, X, X_out, G, nbr, w, n,
+                           d, -lr, lpr);
+    else
+        hipLaunchKernelGGL((mix_step_kernel<1, GT>), dim3(grid), dim3(kThreads), lds_bytes, s, X, X_out, G, nbr, w, n,
+                           d, -lr, lpr);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, name);
+    return PSGD_OK;
+}
+
+int consensus_enqueue(const float* X, int n, int64_t d, double* out_dev, hipStream_t s) {
+    DeviceInfo* di = nullptr;
+    if (int rc = device_info(&di, true)) return rc;
+    const bool vec4 = (d % 4 == 0) && aligned_to(X, 16);
+    const int grid = persistent_grid(*di, vec4 ? d / 4 : d, 8);
+    if (vec4)
+        hipLaunchKernelGGL(consensus_partial_kernel<4>, dim3(grid), dim3(kThreads), 0, s, X, n, d, di->scratch);
+    else
+        hipLaunchKernelGGL(consensus_partial_kernel<1>, dim3(grid), dim3(kThreads), 0, s, X, n, d, di->scratch);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "consensus_partial_kernel");
+    hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, di->scratch, grid,
+                       out_dev ? out_dev : di->scratch + kMaxGrid);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "consensus_final_kernel");
+    return PSGD_OK;
+}
+
+int consensus_check(const char* name, const float* X, int n, int64_t d) {
+    if (!X) return fail(PSGD_EINVAL, "%s: null pointer", name);
+    if (n < 1 || n > PSGD_MAX_N) return fail(PSGD_EINVAL, "%s: n=%d outside 1..%d", name, n, (int)PSGD_MAX_N);
+    if (d < 0) return fail(PSGD_EINVAL, "%s: d=%lld is negative", name, (long long)d);
+    if (!aligned_to(X, 4)) return fail(PSGD_EALIGN, "%s: X not 4-byte aligned", name);
+    if (d > 0 && (int64_t)n > INT64_MAX / 4 / d) return fail(PSGD_EINVAL, "%s: n*d overflows", name);
+    return PSGD_OK;
+}
+
+}  // namespace
+}  // namespace psgd
+
+extern "C" {
+
+int psgd_mix_step(const float* X, float* X_out, const float* G, const int32_t* nbr, const float* w, int n, int64_t d,
+                  float lr, int delay_mode, void* stream) {
+    return psgd::mix_step_impl<float>("psgd_mix_step", X, X_out, G, nbr, w, n, d, lr, delay_mode, stream);
+}
+
+int psgd_mix_step_bf16g(const float* X, float* X_out, const uint16_t* G_bf16, const int32_t* nbr, const float* w,
+                        int n, int64_t d, float lr, int delay_mode, void* stream) {
+    return psgd::mix_step_impl<uint16_t>("psgd_mix_step_bf16g", X, X_out, G_bf16, nbr, w, n, d, lr, delay_mode,
+                                         stream);
+}
+
+double psgd_consensus_dist(const float* X, int n, int64_t d) {
+    using namespace psgd;
+    clear_error();
+    if (consensus_check("psgd_consensus_dist", X, n, d) != PSGD_OK) return NAN;
+    if (d == 0 || n == 1) return 0.0;
+    hipError_t e = hipDeviceSynchronize();
+    if (e != hipSuccess) { hip_fail(e, "hipDeviceSynchronize"); return NAN; }
+    if (consensus_enqueue(X, n, d, nullptr, nullptr) != PSGD_OK) return NAN;
+    DeviceInfo* di = nullptr;
+    if (device_info(&di, true) != PSGD_OK) return NAN;
+    double host = NAN;
+    e = hipMemcpy(&host, di->scratch + kMaxGrid, sizeof(double), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) { hip_fail(e, "hipMemcpy(result)"); return NAN; }
+    return host;
+}
+
+int psgd_consensus_dist_async(const float* X, int n, int64_t d, double* out_dev, void* stream) {
+    using namespace psgd;
+    clear_error();
+    if (!out_dev) return fail(PSGD_EINVAL, "psgd_consensus_dist_async: null output pointer");
+    if (!aligned_to(out_dev, 8)) return fail(PSGD_EALIGN, "psgd_consensus_dist_async: out_dev not 8-byte aligned");
+    if (int rc = consensus_check("psgd_consensus_dist_async", X, n, d)) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (d == 0) {
+        // nothing to reduce: the final kernel over zero partials writes 0
+        DeviceInfo* di = nullptr;
+        if (int rc = device_info(&di, true)) return rc;
+        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, di->scratch, 0, out_dev);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e, "consensus_final_kernel");
+        return PSGD_OK;
+    }
+    return consensus_enqueue(X, n, d, out_dev, s);
+}
+
+int psgd_synth_grad(const float* X_prev, const float* noise, float* G, int64_t count, float c, void* stream) {
+    using namespace psgd;
+    clear_error();
+    if (!X_prev || !noise || !G) return fail(PSGD_EINVAL, "psgd_synth_grad: null pointer");
+    if (count < 0) return fail(PSGD_EINVAL, "psgd_synth_grad: negative count");
+    if (!aligned_to(X_prev, 4) || !aligned_to(noise, 4) || !aligned_to(G, 4))
+        return fail(PSGD_EALIGN, "psgd_synth_grad: pointer not 4-byte aligned");
+    const size_t bytes = (size_t)count * sizeof(float);
+    if (overlaps(G, bytes, X_prev, bytes) || overlaps(G, bytes, noise, bytes))
+        return fail(PSGD_EALIAS, "psgd_synth_grad: G overlaps an input");
+    if (count == 0) return PSGD_OK;
+    DeviceInfo* di = nullptr;
+    if (int rc = device_info(&di, false)) return rc;
+    const int vec4 = aligned_to(X_prev, 16) && aligned_to(noise, 16) && aligned_to(G, 16);
+    const int grid = persistent_grid(*di, vec4 ? (count + 3) / 4 : count, 16);
+    hipLaunchKernelGGL(synth_grad_kernel, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream), X_prev,
+                       noise, G, count, c, vec4);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "synth_grad_kernel");
+    return PSGD_OK;
+}
+
+int psgd_device_status(int clear) {
+    using namespace psgd;
+    clear_error();
+    hipError_t e = hipDeviceSynchronize();
+    if (e != hipSuccess) return hip_fail(e, "hipDeviceSynchronize");
+    int word = 0;
+    e = hipMemcpyFromSymbol(&word, HIP_SYMBOL(g_status_word), sizeof(int));
+    if (e != hipSuccess) return hip_fail(e, "hipMemcpyFromSymbol");
+    if (clear && word) {
+        const int zero = 0;
+        e = hipMemcpyToSymbol(HIP_SYMBOL(g_status_word), &zero, sizeof(int));
+        if (e != hipSuccess) return hip_fail(e, "hipMemcpyToSymbol");
+    }
+    return word;
+}
+
+}  // extern "C"

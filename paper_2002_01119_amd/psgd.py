@@ -1,0 +1,171 @@
+"""ctypes binding of libpsgd.so: argument marshalling only, same names as include/psgd.h.
+
+Device buffers are torch tensors (PyTorch is used for HBM allocation and streams); every
+step of the computation runs in the library's HIP kernels.  There is no fallback: if the
+shared library is missing or a call fails, an exception is raised.
+"""
+import ctypes
+import math
+import os
+
+import numpy as np
+
+TOPO_RING = 0
+TOPO_RAND_RING = 1
+DEG = 3
+MAX_N = 512
+
+OK, EINVAL, EALIAS, EALIGN, EHIP = 0, -1, -2, -3, -4
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libpsgd.so")
+_lib = None
+
+EXPORTS = (
+    "psgd_build_mixing", "psgd_mix_step", "psgd_mix_step_bf16g", "psgd_consensus_dist",
+    "psgd_consensus_dist_async", "psgd_synth_grad", "psgd_device_status", "psgd_last_error",
+    "psgd_version",
+)
+
+
+class PsgdError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("psgd status %d: %s" % (code, text))
+        self.code = code
+
+
+def load(reload=False):
+    """Load libpsgd.so (built in-tree by __graft_entry__.build()) and declare its signatures."""
+    global _lib
+    if _lib is not None and not reload:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError("%s not found: run `python __graft_entry__.py` to build the HIP library"
+                          % _LIB_PATH)
+    lib = ctypes.CDLL(_LIB_PATH)
+    c_i32p = ctypes.POINTER(ctypes.c_int32)
+    c_f32p = ctypes.POINTER(ctypes.c_float)
+    vp = ctypes.c_void_p
+    lib.psgd_build_mixing.restype = ctypes.c_int
+    lib.psgd_build_mixing.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint64,
+                                      c_i32p, c_f32p]
+    for name in ("psgd_mix_step", "psgd_mix_step_bf16g"):
+        fn = getattr(lib, name)
+        fn.restype = ctypes.c_int
+        fn.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int, ctypes.c_int64, ctypes.c_float,
+                       ctypes.c_int, vp]
+    lib.psgd_consensus_dist.restype = ctypes.c_double
+    lib.psgd_consensus_dist.argtypes = [vp, ctypes.c_int, ctypes.c_int64]
+    lib.psgd_consensus_dist_async.restype = ctypes.c_int
+    lib.psgd_consensus_dist_async.argtypes = [vp, ctypes.c_int, ctypes.c_int64, vp, vp]
+    lib.psgd_synth_grad.restype = ctypes.c_int
+    lib.psgd_synth_grad.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_float, vp]
+    lib.psgd_device_status.restype = ctypes.c_int
+    lib.psgd_device_status.argtypes = [ctypes.c_int]
+    lib.psgd_last_error.restype = ctypes.c_char_p
+    lib.psgd_last_error.argtypes = []
+    lib.psgd_version.restype = ctypes.c_int
+    lib.psgd_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def last_error():
+    return load().psgd_last_error().decode("utf-8", "replace")
+
+
+def _check(rc):
+    if rc != OK:
+        raise PsgdError(rc, last_error())
+
+
+def _stream_handle(stream):
+    """hipStream_t of a torch stream (None = torch's current stream)."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _rows_cols(t):
+    if t.dim() != 2 or not t.is_contiguous():
+        raise ValueError("expected a contiguous [n, d] tensor")
+    return int(t.shape[0]), int(t.shape[1])
+
+
+def build_mixing(topology, n, seed=0, step=0):
+    """Returns (nbr int32 [n,3], w float32 [n,3]) as host numpy arrays."""
+    nbr = np.empty((max(n, 0), DEG), dtype=np.int32)
+    w = np.empty((max(n, 0), DEG), dtype=np.float32)
+    _check(load().psgd_build_mixing(
+        int(topology), int(n), ctypes.c_uint64(seed & (2 ** 64 - 1)), ctypes.c_uint64(step & (2 ** 64 - 1)),
+        nbr.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), w.ctypes.data_as(ctypes.POINTER(ctypes.c_float))))
+    return nbr, w
+
+
+def mix_step(X, X_out, G, nbr, w, lr, delay_mode=0, stream=None):
+    """Enqueue X_out = mix(X) - lr * G.  All arguments are device tensors; G is float32, or
+    bfloat16 / int16 / uint16 (bf16 bit patterns), which selects psgd_mix_step_bf16g."""
+    import torch
+    n, d = _rows_cols(X)
+    if tuple(X_out.shape) != (n, d) or tuple(G.shape) != (n, d) or not X_out.is_contiguous() \
+            or not G.is_contiguous():
+        raise ValueError("X, X_out and G must be contiguous and of one shape")
+    if X.dtype != torch.float32 or X_out.dtype != torch.float32:
+        raise ValueError("X and X_out must be float32")
+    if nbr.dtype != torch.int32 or w.dtype != torch.float32 or nbr.numel() != n * DEG \
+            or w.numel() != n * DEG or not nbr.is_contiguous() or not w.is_contiguous():
+        raise ValueError("nbr must be int32 [n,3] and w float32 [n,3], contiguous")
+    for t in (X_out, G, nbr, w):
+        if t.device != X.device:
+            raise ValueError("all tensors must live on one device")
+    lib = load()
+    if G.dtype == torch.float32:
+        fn = lib.psgd_mix_step
+    elif G.dtype in (torch.bfloat16, torch.int16, torch.uint16):
+        fn = lib.psgd_mix_step_bf16g
+    else:
+        raise ValueError("G must be float32 or bfloat16 bit patterns")
+    _check(fn(X.data_ptr(), X_out.data_ptr(), G.data_ptr(), nbr.data_ptr(), w.data_ptr(), n, d,
+              float(lr), int(delay_mode), _stream_handle(stream)))
+
+
+def consensus_dist(X):
+    """Synchronous sum_i ||x_i - xbar||^2 of a device tensor [n, d]."""
+    n, d = _rows_cols(X)
+    v = load().psgd_consensus_dist(X.data_ptr(), n, d)
+    if math.isnan(v):
+        err = last_error()
+        if err:
+            raise PsgdError(EINVAL, err)
+    return v
+
+
+def consensus_dist_async(X, out, stream=None):
+    """Enqueue the consensus distance of X into out (device float64 tensor, 1 element)."""
+    import torch
+    n, d = _rows_cols(X)
+    if out.dtype != torch.float64 or out.numel() < 1 or out.device != X.device:
+        raise ValueError("out must be a float64 device tensor")
+    _check(load().psgd_consensus_dist_async(X.data_ptr(), n, d, out.data_ptr(), _stream_handle(stream)))
+
+
+def synth_grad(X_prev, noise, G, c, stream=None):
+    """Enqueue G = c * X_prev + noise (fp32, elementwise) for the delay-by-one workload."""
+    if X_prev.numel() != noise.numel() or X_prev.numel() != G.numel():
+        raise ValueError("X_prev, noise and G must have the same number of elements")
+    for t in (X_prev, noise, G):
+        if not t.is_contiguous():
+            raise ValueError("tensors must be contiguous")
+    _check(load().psgd_synth_grad(X_prev.data_ptr(), noise.data_ptr(), G.data_ptr(), X_prev.numel(),
+                                  float(c), _stream_handle(stream)))
+
+
+def device_status(clear=True):
+    rc = load().psgd_device_status(1 if clear else 0)
+    if rc < 0:
+        raise PsgdError(rc, last_error())
+    return rc
+
+
+def version():
+    return load().psgd_version()

@@ -1,0 +1,301 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, on seeded inputs.
+
+Tolerances (stated by the baseline: relative 1e-6 with fp32 accumulation).  One step does
+four fp32 roundings on partial sums bounded by ||X||_inf + lr ||G||_inf, so the absolute
+error per element is at most 4 * 2^-24 * that bound = 2.4e-7 of the largest magnitude.
+"Relative" is therefore taken against the largest output magnitude (element-wise relative
+error is unbounded where an output is near zero), plus the Frobenius-norm ratio.
+"""
+import numpy as np
+import pytest
+
+from oracle import psgd_oracle as orc
+from paper_2002_01119_amd import inputs as inp
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+REL = 1e-6
+
+
+@pytest.fixture(scope="module")
+def psgd():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2002_01119_amd import psgd as m
+    m.load()          # raises if the HIP library is not built: no fallback
+    torch.cuda.set_device(0)
+    return m
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def bits_dev(bits_u16):
+    return torch.from_numpy(bits_u16.view(np.int16)).to("cuda:0")
+
+
+def assert_close(got, want, rel=REL):
+    got = np.asarray(got, dtype=np.float64)
+    scale = max(np.abs(want).max(), 1e-30)
+    err = np.abs(got - want).max()
+    assert err <= rel * scale, "max abs err %.3g vs scale %.3g" % (err, scale)
+    fro = np.linalg.norm(want)
+    if fro > 0:
+        assert np.linalg.norm(got - want) <= rel * fro
+
+
+def run_step(psgd, X, G, nbr, w, lr, in_place=False, delay_mode=0):
+    Xd = dev(X)
+    Gd = bits_dev(G) if G.dtype == np.uint16 else dev(G)
+    out = Xd if in_place else torch.full_like(Xd, float("nan"))
+    psgd.mix_step(Xd, out, Gd, dev(nbr), dev(w), lr, delay_mode=delay_mode)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+SHAPES = [(1, 1), (1, 1000), (2, 5), (3, 4), (4, 7), (5, 1024), (8, 4100), (8, 70001),
+          (16, 3 * 1024 * 4 + 4), (33, 2052), (64, 9 * 1024 + 8), (128, 4096 + 12), (512, 260)]
+
+
+@pytest.mark.parametrize("n,d", SHAPES)
+@pytest.mark.parametrize("topo", [orc.TOPO_RING, orc.TOPO_RAND_RING])
+@pytest.mark.parametrize("gkind", ["f32", "bf16"])
+def test_single_step_matches_oracle(psgd, n, d, topo, gkind):
+    X = inp.host_normal_f32((n, d), 1.0, 100 + n)
+    G = inp.host_normal_f32((n, d), 0.5, 200 + n)
+    if gkind == "bf16":
+        G = inp.f32_to_bf16_bits(G)
+    nbr, w = psgd.build_mixing(topo, n, seed=9, step=n + d)
+    want = orc.mix_step(X, G, orc.densify(nbr, w), 0.1)
+    got = run_step(psgd, X, G, nbr, w, 0.1)
+    assert not np.isnan(got).any()
+    assert_close(got, want)
+    got_ip = run_step(psgd, X, G, nbr, w, 0.1, in_place=True)
+    assert np.array_equal(got_ip.view(np.uint32), got.view(np.uint32))     # same kernel, same bits
+    got_d1 = run_step(psgd, X, G, nbr, w, 0.1, delay_mode=1)
+    assert np.array_equal(got_d1.view(np.uint32), got.view(np.uint32))
+    assert psgd.device_status() == 0
+
+
+def test_exact_fp32_operation_order(psgd):
+    """The header fixes the fp32 operation order; reproduce it with numpy fp32 scalars
+    (fma emulated in fp64, which is exact for one fp32 product plus one addend up to the
+    final rounding) and demand bit equality."""
+    n, d = 8, 515
+    X = inp.host_normal_f32((n, d), 1.0, 1)
+    G = inp.host_normal_f32((n, d), 1.0, 2)
+    nbr, w = psgd.build_mixing(psgd.TOPO_RAND_RING, n, 5, 5)
+    lr = np.float32(0.05)
+    got = run_step(psgd, X, G, nbr, w, float(lr))
+
+    def fma32(a, b, c):
+        return (a.astype(np.float64) * b.astype(np.float64) + c.astype(np.float64)).astype(np.float32)
+
+    want = np.empty_like(X)
+    for i in range(n):
+        acc = (X[nbr[i, 0]] * w[i, 0]).astype(np.float32)
+        acc = fma32(np.broadcast_to(w[i, 1], (d,)), X[nbr[i, 1]], acc)
+        acc = fma32(np.broadcast_to(w[i, 2], (d,)), X[nbr[i, 2]], acc)
+        want[i] = fma32(np.broadcast_to(-lr, (d,)), G[i], acc)
+    # double rounding in the emulation can differ from a true fma in rare ties: allow 1 ulp
+    # on a handful of elements, bit equality on the rest
+    diff = np.abs(got.view(np.int32).astype(np.int64) - want.view(np.int32).astype(np.int64))
+    assert diff.max() <= 1 and (diff > 0).mean() < 1e-3
+
+
+def _general_table(n, rng, weights=(0.5, 0.3, 0.2)):
+    """A doubly stochastic 3-slot table that is not a ring: w0 I + w1 P1 + w2 P2."""
+    p1, p2 = rng.permutation(n), rng.permutation(n)
+    nbr = np.stack([np.arange(n), p1, p2], axis=1).astype(np.int32)
+    w = np.tile(np.asarray(weights, dtype=np.float32), (n, 1))
+    return nbr, w
+
+
+@pytest.mark.parametrize("n,d", [(4, 9), (6, 2048), (16, 4 * 3000), (64, 1025), (128, 8192 + 4), (300, 516)])
+@pytest.mark.parametrize("gkind", ["f32", "bf16"])
+def test_general_tables_use_the_tiled_path(psgd, n, d, gkind):
+    rng = np.random.default_rng(n * 7 + d)
+    nbr, w = _general_table(n, rng)
+    T = orc.densify(nbr, w)
+    assert np.allclose(T.sum(0), 1, atol=1e-6) and np.allclose(T.sum(1), 1, atol=1e-6)
+    X = inp.host_normal_f32((n, d), 1.0, 300 + n)
+    G = inp.host_normal_f32((n, d), 0.5, 400 + n)
+    if gkind == "bf16":
+        G = inp.f32_to_bf16_bits(G)
+    want = orc.mix_step(X, G, T, 0.2)
+    got = run_step(psgd, X, G, nbr, w, 0.2)
+    assert_close(got, want)
+    got_ip = run_step(psgd, X, G, nbr, w, 0.2, in_place=True)
+    assert np.array_equal(got_ip.view(np.uint32), got.view(np.uint32))
+
+
+def test_two_disjoint_rings_and_self_loops(psgd):
+    """Locally consistent left/right pointers that do not form ONE ring must not take the
+    ring walk: two rings of 4, and the all-self table (identity mixing)."""
+    n, d = 8, 1030
+    nbr = np.zeros((n, 3), np.int32)
+    for base in (0, 4):
+        for k in range(4):
+            i = base + k
+            nbr[i] = (i, base + (k - 1) % 4, base + (k + 1) % 4)
+    w = np.full((n, 3), 1 / 3, np.float32)
+    X = inp.host_normal_f32((n, d), 1.0, 31)
+    G = inp.host_normal_f32((n, d), 1.0, 32)
+    assert_close(run_step(psgd, X, G, nbr, w, 0.1), orc.mix_step(X, G, orc.densify(nbr, w), 0.1))
+    ident = np.repeat(np.arange(n, dtype=np.int32)[:, None], 3, axis=1)
+    assert_close(run_step(psgd, X, G, ident, w, 0.1), orc.mix_step(X, G, orc.densify(ident, w), 0.1))
+
+
+def test_ring_with_per_row_weights(psgd):
+    """The ring walk carries each row's own three weights (a lazy-walk style table)."""
+    n, d = 16, 2056
+    nbr, _ = psgd.build_mixing(psgd.TOPO_RAND_RING, n, 1, 2)
+    rng = np.random.default_rng(5)
+    w = rng.random((n, 3)).astype(np.float32)
+    X = inp.host_normal_f32((n, d), 1.0, 41)
+    G = inp.host_normal_f32((n, d), 1.0, 42)
+    assert_close(run_step(psgd, X, G, nbr, w, 0.3), orc.mix_step(X, G, orc.densify(nbr, w), 0.3))
+
+
+def test_out_of_range_table_is_flagged_and_writes_nothing(psgd):
+    n, d = 8, 4096
+    nbr, w = psgd.build_mixing(psgd.TOPO_RING, n)
+    nbr = nbr.copy()
+    nbr[3, 2] = n            # one past the end
+    X = inp.host_normal_f32((n, d), 1.0, 51)
+    G = inp.host_normal_f32((n, d), 1.0, 52)
+    assert psgd.device_status() == 0
+    out = run_step(psgd, X, G, nbr, w, 0.1)
+    assert np.isnan(out).all()
+    assert psgd.device_status(clear=True) == 1
+    assert psgd.device_status() == 0
+    nbr[3, 2] = -1
+    out = run_step(psgd, X, G, nbr, w, 0.1)
+    assert np.isnan(out).all() and psgd.device_status(clear=True) == 1
+
+
+def test_binding_reports_alias_errors(psgd):
+    X = torch.zeros(4, 64, device="cuda:0")
+    G = torch.zeros(4, 64, device="cuda:0")
+    nbr, w = psgd.build_mixing(psgd.TOPO_RING, 4)
+    with pytest.raises(psgd.PsgdError) as e:
+        psgd.mix_step(X, X, G, dev(nbr), dev(w), 0.1, delay_mode=1)
+    assert e.value.code == psgd.EALIAS
+    with pytest.raises(psgd.PsgdError):
+        psgd.mix_step(X, G, G, dev(nbr), dev(w), 0.1)
+    psgd.mix_step(X, X, G, dev(nbr), dev(w), 0.1, delay_mode=0)
+    torch.cuda.synchronize()
+
+
+def test_misaligned_views_take_the_scalar_path(psgd):
+    """Buffers that are only 4-byte aligned (and 2-byte for bf16) must still be right."""
+    n, d = 8, 1001
+    X = inp.host_normal_f32((n, d), 1.0, 61)
+    G = inp.host_normal_f32((n, d), 1.0, 62)
+    Gb = inp.f32_to_bf16_bits(G)
+    nbr, w = psgd.build_mixing(psgd.TOPO_RAND_RING, n, 4, 4)
+    pad = torch.zeros(n * d + 1, device="cuda:0")
+    pad[1:] = dev(X).reshape(-1)
+    Xv = pad[1:].view(n, d)
+    assert Xv.data_ptr() % 16 == 4
+    out = torch.empty(n * d + 3, device="cuda:0")[3:].view(n, d)
+    gpad = torch.zeros(n * d + 1, dtype=torch.int16, device="cuda:0")
+    gpad[1:] = bits_dev(Gb).reshape(-1)
+    Gv = gpad[1:].view(n, d)
+    psgd.mix_step(Xv, out, Gv, dev(nbr), dev(w), 0.1)
+    torch.cuda.synchronize()
+    assert_close(out.cpu().numpy(), orc.mix_step(X, Gb, orc.densify(nbr, w), 0.1))
+
+
+# ------------------------------------------------------------------------- consensus distance
+@pytest.mark.parametrize("n,d", [(1, 10), (2, 1), (3, 5), (8, 4096), (8, 70001), (16, 12 * 1024 + 4),
+                                 (64, 50_000), (128, 10_004), (17, 1023), (512, 300)])
+def test_consensus_matches_oracle(psgd, n, d):
+    X = inp.host_normal_f32((n, d), 0.05, 500 + n)
+    want = orc.consensus_dist(X)
+    got = psgd.consensus_dist(dev(X))
+    assert abs(got - want) <= REL * max(want, 1e-300)
+    out = torch.zeros(1, dtype=torch.float64, device="cuda:0")
+    psgd.consensus_dist_async(dev(X), out)
+    torch.cuda.synchronize()
+    assert out.item() == got            # same kernels, fixed reduction order
+
+
+def test_consensus_closed_forms_and_offsets(psgd):
+    assert psgd.consensus_dist(dev(np.tile(np.arange(1000, dtype=np.float32), (7, 1)))) == 0.0
+    for n, d in [(2, 3), (8, 1000), (64, 4096), (128, 1001)]:
+        X = np.repeat(np.arange(n, dtype=np.float32)[:, None], d, axis=1)
+        assert psgd.consensus_dist(dev(X)) == d * n * (n * n - 1) / 12
+    # replicas that sit far from the origin but close to each other: a one-pass sum of
+    # squares in fp32 would lose everything here
+    base = inp.host_normal_f32((1, 5000), 100.0, 71)
+    X = (base + inp.host_normal_f32((16, 5000), 1e-3, 72)).astype(np.float32)
+    want = orc.consensus_dist(X)
+    assert abs(psgd.consensus_dist(dev(X)) - want) <= REL * want
+    # an outlier in the pivot row (row 0)
+    X = inp.host_normal_f32((32, 3000), 1.0, 73)
+    X[0] += 1000.0
+    want = orc.consensus_dist(X)
+    assert abs(psgd.consensus_dist(dev(X)) - want) <= REL * want
+
+
+def test_consensus_is_reproducible(psgd):
+    X = dev(inp.host_normal_f32((64, 300_000), 0.02, 81))
+    vals = {psgd.consensus_dist(X) for _ in range(5)}
+    assert len(vals) == 1
+
+
+# ------------------------------------------------------------------------- gradient producer
+def test_synth_grad_matches_oracle(psgd):
+    for count in (1, 5, 4096, 100_003):
+        Xp = inp.host_normal_f32((count,), 0.02, 91)
+        Z = inp.host_normal_f32((count,), 1e-3, 92)
+        G = torch.empty(count, device="cuda:0")
+        psgd.synth_grad(dev(Xp), dev(Z), G, 0.01)
+        torch.cuda.synchronize()
+        want = orc.synth_grad(Xp, Z, 0.01)
+        assert_close(G.cpu().numpy(), want, rel=2.0 ** -23)
+
+
+# ------------------------------------------------------------------------- short trajectories
+@pytest.mark.parametrize("topo", [orc.TOPO_RING, orc.TOPO_RAND_RING])
+def test_cfg1_full_trajectory_every_element(psgd, topo):
+    """Workload 1 (n = 8, d = 1e6, 10 steps), every element of every step, free-running on
+    both sides from the same X_0 and the same per-step gradients, plus the consensus
+    distance after each step and the mean invariant."""
+    wl = inp.workload(1)
+    X0 = inp.host_normal_f32((wl.n, wl.d), wl.sigma_x, wl.seed_x)
+    Xd, Yd = dev(X0), torch.empty(wl.n, wl.d, device="cuda:0")
+    Xo = X0.astype(np.float64)
+    for k in range(wl.steps):
+        G = inp.host_normal_f32((wl.n, wl.d), wl.sigma_g, wl.seed_g * 1000 + k)
+        nbr, w = psgd.build_mixing(topo, wl.n, wl.seed_perm, k)
+        psgd.mix_step(Xd, Yd, dev(G), dev(nbr), dev(w), wl.lr)
+        Xd, Yd = Yd, Xd
+        Xo = orc.mix_step(Xo, G, orc.densify(nbr, w), wl.lr)
+        got = Xd.cpu().numpy()
+        assert_close(got, Xo)
+        c_gpu, c_ref = psgd.consensus_dist(Xd), orc.consensus_dist(got)
+        assert abs(c_gpu - c_ref) <= REL * c_ref
+        assert abs(c_gpu - orc.consensus_dist(Xo)) <= 1e-5 * c_ref
+    # expected value for a Gaussian start (fixed ring): C_10 ~ 2.596e4; random ring far lower
+    if topo == orc.TOPO_RING:
+        assert abs(c_gpu / 2.596e4 - 1) < 0.02
+
+
+def test_mean_preserved_at_zero_lr(psgd):
+    """Doubly stochastic mixing keeps the replica mean; with fl32(1/3) weights the drift is
+    3 fl32(1/3) - 1 = 3e-8 per step, common to oracle and GPU."""
+    n, d, steps = 16, 40_000, 20
+    X0 = inp.host_normal_f32((n, d), 1.0, 7) + np.float32(3.0)
+    G = torch.zeros(n, d, device="cuda:0")
+    Xd = dev(X0)
+    for k in range(steps):
+        nbr, w = psgd.build_mixing(psgd.TOPO_RAND_RING, n, 12, k)
+        psgd.mix_step(Xd, Xd, G, dev(nbr), dev(w), 0.0)
+    torch.cuda.synchronize()
+    m0 = X0.astype(np.float64).mean(0)
+    m1 = Xd.cpu().numpy().astype(np.float64).mean(0)
+    assert np.abs(m1 - m0).max() <= steps * 1e-7 * np.abs(m0).max()

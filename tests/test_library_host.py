@@ -1,0 +1,133 @@
+"""CPU-only checks of the C boundary: the library loads, exports what include/psgd.h declares,
+builds tables bit-identical to the oracle's, and rejects bad arguments before touching a
+device.  No kernel runs here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import psgd_oracle as orc
+from paper_2002_01119_amd import psgd
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = psgd.load()
+    with open(os.path.join(ROOT, "include", "psgd.h")) as f:
+        text = re.sub(r"/\*.*?\*/", "", f.read(), flags=re.S)
+    declared = sorted(set(re.findall(r"\b(psgd_[a-z0-9_]+)\s*\(", text)))
+    assert len(declared) >= 9
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert sorted(psgd.EXPORTS) == declared
+    assert psgd.version() >= 1
+    assert psgd.MAX_N == 512 and psgd.DEG == 3
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 8, 16, 33, 64, 128, 512])
+def test_tables_bit_identical_to_oracle(n):
+    for topo in (psgd.TOPO_RING, psgd.TOPO_RAND_RING):
+        for seed in (0, 1, 3001, 3005, 2 ** 63 + 5, 2 ** 64 - 1):
+            for step in (0, 1, 7, 99, 2 ** 40 + 3):
+                nbr, w = psgd.build_mixing(topo, n, seed, step)
+                onbr, ow = orc.neighbour_table(topo, n, seed, step)
+                assert nbr.dtype == np.int32 and w.dtype == np.float32
+                assert np.array_equal(nbr, onbr), (topo, n, seed, step)
+                assert np.array_equal(w.view(np.uint32), ow.view(np.uint32))
+
+
+def test_tables_match_frozen_golden(golden_dir):
+    with open(os.path.join(golden_dir, "mixing_tables.txt")) as f:
+        lines = [l for l in f if l.strip() and not l.startswith("#")]
+    for line in lines:
+        head, rest = line.split(":")
+        n, seed, step = (int(x) for x in head.split())
+        nbr, _ = psgd.build_mixing(psgd.TOPO_RAND_RING, n, seed, step)
+        assert [int(v) for v in nbr.reshape(-1)] == [int(x) for x in rest.split("|")[1].split()]
+
+
+def test_tables_same_seed_same_ring_and_ring_ignores_seed():
+    a = psgd.build_mixing(psgd.TOPO_RAND_RING, 64, 42, 5)[0]
+    b = psgd.build_mixing(psgd.TOPO_RAND_RING, 64, 42, 5)[0]
+    c = psgd.build_mixing(psgd.TOPO_RAND_RING, 64, 42, 6)[0]
+    assert np.array_equal(a, b) and not np.array_equal(a, c)
+    assert np.array_equal(psgd.build_mixing(psgd.TOPO_RING, 9, 1, 2)[0],
+                          psgd.build_mixing(psgd.TOPO_RING, 9, 3, 4)[0])
+
+
+def test_build_mixing_rejects_bad_arguments():
+    lib = psgd.load()
+    nbr = (ctypes.c_int32 * 12)()
+    w = (ctypes.c_float * 12)()
+    assert lib.psgd_build_mixing(0, 0, 0, 0, nbr, w) == psgd.EINVAL
+    assert "n=0" in psgd.last_error()
+    assert lib.psgd_build_mixing(0, psgd.MAX_N + 1, 0, 0, nbr, w) == psgd.EINVAL
+    assert lib.psgd_build_mixing(7, 4, 0, 0, nbr, w) == psgd.EINVAL
+    assert "topology" in psgd.last_error()
+    assert lib.psgd_build_mixing(0, 4, 0, 0, None, w) == psgd.EINVAL
+    assert lib.psgd_build_mixing(0, 4, 0, 0, nbr, None) == psgd.EINVAL
+    assert lib.psgd_build_mixing(0, 4, 0, 0, nbr, w) == psgd.OK
+    assert psgd.last_error() == ""
+    with pytest.raises(psgd.PsgdError):
+        psgd.build_mixing(psgd.TOPO_RING, 0)
+
+
+def test_mix_step_argument_checks_need_no_device():
+    """Validation runs before any HIP call, so fake (never dereferenced) addresses do."""
+    lib = psgd.load()
+    A, B, C, T1, T2 = 0x100000, 0x900000, 0x1100000, 0x2000000, 0x2001000
+    n, d = 4, 1000
+
+    def call(fn=lib.psgd_mix_step, X=A, O=B, G=C, nbr=T1, w=T2, n=n, d=d, lr=0.1, mode=0):
+        return fn(X, O, G, nbr, w, n, d, lr, mode, None)
+
+    assert call(X=None) == psgd.EINVAL and "null" in psgd.last_error()
+    assert call(O=None) == psgd.EINVAL
+    assert call(G=None) == psgd.EINVAL
+    assert call(nbr=None) == psgd.EINVAL
+    assert call(w=None) == psgd.EINVAL
+    assert call(n=0) == psgd.EINVAL
+    assert call(n=psgd.MAX_N + 1) == psgd.EINVAL
+    assert call(d=-1) == psgd.EINVAL
+    assert call(mode=2) == psgd.EINVAL
+    assert call(n=512, d=2 ** 61) == psgd.EINVAL and "overflow" in psgd.last_error()
+    assert call(X=A + 2) == psgd.EALIGN
+    assert call(G=C + 1) == psgd.EALIGN
+    assert call(fn=lib.psgd_mix_step_bf16g, G=C + 1) == psgd.EALIGN
+    assert call(O=A + 16) == psgd.EALIAS and "partially" in psgd.last_error()
+    assert call(O=A, mode=1) == psgd.EALIAS and "delay" in psgd.last_error()
+    assert call(G=B + 4 * 100) == psgd.EALIAS
+    # an empty model is a no-op that needs no device either; in-place is legal in mode 0
+    assert call(d=0) == psgd.OK
+    assert call(O=A, d=0) == psgd.OK
+
+
+def test_other_entry_points_argument_checks():
+    lib = psgd.load()
+    A = 0x100000
+    assert np.isnan(lib.psgd_consensus_dist(None, 4, 10))
+    assert "null" in psgd.last_error()
+    assert np.isnan(lib.psgd_consensus_dist(A, 0, 10))
+    assert np.isnan(lib.psgd_consensus_dist(A + 1, 4, 10))
+    assert lib.psgd_consensus_dist(A, 1, 10) == 0.0          # one learner is always at consensus
+    assert lib.psgd_consensus_dist(A, 4, 0) == 0.0
+    assert lib.psgd_consensus_dist_async(A, 4, 10, None, None) == psgd.EINVAL
+    assert lib.psgd_consensus_dist_async(A, 4, 10, A + 4, None) == psgd.EALIGN
+    assert lib.psgd_consensus_dist_async(None, 4, 10, A, None) == psgd.EINVAL
+    assert lib.psgd_synth_grad(None, A, A, 10, 0.1, None) == psgd.EINVAL
+    assert lib.psgd_synth_grad(A, A + 4096, A + 8, 10, 0.1, None) == psgd.EALIAS
+    assert lib.psgd_synth_grad(A, A + 4096, A + 8192, -1, 0.1, None) == psgd.EINVAL
+    assert lib.psgd_synth_grad(A, A + 4096, A + 8192, 0, 0.1, None) == psgd.OK
+
+
+def test_no_device_is_reported_not_crashed():
+    """On a box without a GPU a real launch request must come back as PSGD_EHIP."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    lib = psgd.load()
+    rc = lib.psgd_mix_step(0x100000, 0x900000, 0x1100000, 0x2000000, 0x2001000, 4, 1000, 0.1, 0, None)
+    assert rc == psgd.EHIP and psgd.last_error() != ""
