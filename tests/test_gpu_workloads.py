@@ -43,12 +43,13 @@ def pull(t, cols_t):
     return s.cpu().numpy()
 
 
-def assert_close(got, want, rel=REL):
+def assert_close(got, want, rel=REL, scale=None, fro=None):
     got = np.asarray(got, dtype=np.float64)
-    scale = max(np.abs(want).max(), 1e-30)
+    scale = max(np.abs(want).max(), 1e-30) if scale is None else scale
+    fro = np.linalg.norm(want) if fro is None else fro
     err = np.abs(got - want).max()
     assert err <= rel * scale, "max abs err %.3g vs scale %.3g" % (err, scale)
-    assert np.linalg.norm(got - want) <= rel * np.linalg.norm(want)
+    assert np.linalg.norm(got - want) <= rel * fro
 
 
 def expected_consensus(Ts, d, sigma_x, sigma_g, lr):
@@ -102,6 +103,12 @@ def run_workload(psgd, wl, topo, steps=None):
         X_prev = X.clone()              # X_{-1} := X_0
     gen = torch.Generator(device="cuda:0")
     gen.manual_seed(wl.seed_g)
+    # A free-running trajectory is compared relative to the largest magnitude it has held:
+    # averaging with a doubly stochastic matrix never amplifies an earlier rounding error
+    # (its infinity norm is 1) but it does shrink the values, so an error injected while
+    # |X| was large stays visible after |X| has contracted.  Worst case after k steps is
+    # 4 * 2^-24 * k of that magnitude; the roundings are independent, so sqrt(k) is what shows.
+    scale_hist, fro_hist = np.abs(Xo).max(), np.linalg.norm(Xo)
     cdist, Ts = [], []
     c_out = torch.zeros(steps, dtype=torch.float64, device="cuda:0")
     for k in range(steps):
@@ -128,8 +135,12 @@ def run_workload(psgd, wl, topo, steps=None):
             X_prev, X, Y = X, Y, X_prev      # three buffers rotate: X_{k-1}, X_k, X_{k+1}
         else:
             X, Y = Y, X
-        if k < 3 or k == steps - 1 or k % 10 == 0:
-            assert_close(pull(X, cols_t), Xo)
+        scale_hist = max(scale_hist, np.abs(Xo).max())
+        fro_hist = max(fro_hist, np.linalg.norm(Xo))
+        if k == 0:
+            assert_close(pull(X, cols_t), Xo)          # one step from identical inputs
+        elif k < 3 or k == steps - 1 or k % 10 == 0:
+            assert_close(pull(X, cols_t), Xo, scale=scale_hist, fro=fro_hist)
     torch.cuda.synchronize()
     assert psgd.device_status() == 0
     cdist = c_out.cpu().numpy()
