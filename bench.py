@@ -1,0 +1,220 @@
+#!/usr/bin/env python3
+"""Benchmark of the decentralized-SGD model-averaging hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic input, with X and
+G already resident in HBM:
+    build the iteration's mixing table on the host (seeded random ring)   -> upload it
+    fused mix + SGD kernel  X_out = mix(X) - lr * G                       (Sec. 2, Eq. 2)
+    consensus distance of X_out                                            (Sec. 3)
+    swap the X buffers (and rotate the gradient buffers)
+Default workload: n = 64 learners, d = 100,000,000 parameters, bf16 gradients, randomized
+ring (the configuration the 80 %-of-HBM target is quoted on).
+
+Prints ONE JSON line on stdout; progress and per-kernel detail go to stderr.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+# HBM bytes per launch of the mix kernel on workload 5 from two rocprofv3 --pmc runs
+# (FETCH_SIZE, then WRITE_SIZE), each scaled by the same counter's reading for a plain copy
+# of known size; None until measured for a workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(wl, seconds_budget=20.0):
+    """The oracle as it stands, timed on the host: whole hot-path step (dense-matrix update
+    in fp64 + two-pass consensus distance) on a column slice of the same workload."""
+    import numpy as np
+    from oracle import psgd_oracle as orc
+    from paper_2002_01119_amd import inputs as inp
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    cols = min(wl.d, 1_000_000)
+    X = inp.host_normal_f32((wl.n, cols), wl.sigma_x, wl.seed_x)
+    if wl.g_dtype == "bf16":
+        G = inp.host_normal_bf16_bits((wl.n, cols), wl.sigma_g, wl.seed_g)
+    else:
+        G = inp.host_normal_f32((wl.n, cols), wl.sigma_g, wl.seed_g)
+    steps, elapsed = 0, 0.0
+    while steps < 2 or (elapsed < seconds_budget / 2 and steps < 8):
+        t0 = time.perf_counter()
+        T = orc.mixing_matrix(wl.topology, wl.n, wl.seed_perm, steps)
+        Xn = orc.mix_step(X, G, T, wl.lr)
+        orc.consensus_dist(Xn)
+        elapsed += time.perf_counter() - t0
+        X = Xn.astype(np.float32)
+        steps += 1
+    return {
+        "value": wl.n * cols * steps / elapsed,
+        "unit": "updates/s",
+        "cores": threads,
+        "kind": "oracle",
+        "sample": "first %d of %d columns x all %d learners, %d steps (columns are independent; "
+                  "dense fp64 mixing-matrix product + two-pass consensus distance, numpy)"
+                  % (cols, wl.d, wl.n, steps),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=5, help="1..5, the synthetic workload table")
+    ap.add_argument("--no-consensus", action="store_true", help="leave the consensus distance out of the step")
+    ap.add_argument("--in-place", action="store_true", help="mix in place instead of ping-pong buffers")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs all learners on ONE GPU (no collectives); --gpus %d is not "
+            "supported, run with --gpus 1" % args.gpus)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2002_01119_amd import inputs as inp
+    from paper_2002_01119_amd import psgd
+
+    psgd.load()                      # no fallback: fails loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(3)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    wl = inp.workload(args.workload)
+    n, d = wl.n, wl.d
+    K, W = args.steps, args.warmup
+    total = K + W
+    log("workload %s: n=%d d=%d G=%s steps=%d warmup=%d" % (wl.name, n, d, wl.g_dtype, K, W))
+
+    # ---- resident inputs
+    X = inp.device_normal_f32((n, d), wl.sigma_x, wl.seed_x, dev)
+    Y = X if args.in_place else torch.empty_like(X)
+    if wl.g_dtype == "bf16":
+        Gs = [inp.device_normal_bf16((n, d), wl.sigma_g, wl.seed_g + i, dev) for i in range(2)]
+    else:
+        Gs = [inp.device_normal_f32((n, d), wl.sigma_g, wl.seed_g + i, dev) for i in range(2)]
+    noise = None
+    if wl.delay:                      # delay-by-one: G_k = c * X_{k-1} + noise, three X buffers
+        noise = inp.device_normal_f32((n, d), wl.sigma_g, wl.seed_g + 7, dev)
+    X_prev = X.clone() if wl.delay else None
+    nbr_host = torch.empty((total, n, 3), dtype=torch.int32, pin_memory=True)
+    w_host = torch.empty((total, n, 3), dtype=torch.float32, pin_memory=True)
+    nbr_dev = torch.empty((total, n, 3), dtype=torch.int32, device=dev)
+    w_dev = torch.empty((total, n, 3), dtype=torch.float32, device=dev)
+    cdist = torch.zeros(total, dtype=torch.float64, device=dev)
+    stream = torch.cuda.Stream(device=dev)
+    ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(total)]
+    ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(total)]
+    ev2 = [torch.cuda.Event(enable_timing=True) for _ in range(total)]
+    torch.cuda.synchronize()
+
+    def one_step(k):
+        nonlocal X, Y, X_prev
+        nbr, w = psgd.build_mixing(wl.topology, n, wl.seed_perm, k)
+        nbr_host[k].copy_(torch.from_numpy(nbr))
+        w_host[k].copy_(torch.from_numpy(w))
+        nbr_dev[k].copy_(nbr_host[k], non_blocking=True)
+        w_dev[k].copy_(w_host[k], non_blocking=True)
+        G = Gs[k % 2]
+        if wl.delay:
+            psgd.synth_grad(X_prev, noise, G, wl.grad_pull, stream=stream)
+        ev0[k].record(stream)
+        psgd.mix_step(X, Y, G, nbr_dev[k], w_dev[k], wl.lr, delay_mode=1 if wl.delay else 0, stream=stream)
+        ev1[k].record(stream)
+        if not args.no_consensus:
+            psgd.consensus_dist_async(Y, cdist[k:k + 1], stream=stream)
+        ev2[k].record(stream)
+        if wl.delay:
+            X_prev, X, Y = X, Y, X_prev
+        elif not args.in_place:
+            X, Y = Y, X
+
+    with torch.cuda.stream(stream):
+        for k in range(W):
+            one_step(k)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(W, total):
+            one_step(k)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    if psgd.device_status() != 0:
+        log("bench.py: a kernel flagged an invalid mixing table")
+        sys.exit(4)
+
+    wall = t1 - t0
+    mix_ms = [ev0[k].elapsed_time(ev1[k]) for k in range(W, total)]
+    con_ms = [ev1[k].elapsed_time(ev2[k]) for k in range(W, total)]
+    mix_avg = sum(mix_ms) / len(mix_ms)
+    con_avg = sum(con_ms) / len(con_ms)
+    bytes_per_update = 10 if wl.g_dtype == "bf16" else 12       # X read + G read + X_out write
+    mix_bytes = bytes_per_update * n * d
+    achieved = mix_bytes / (mix_avg * 1e-3) / 1e9
+    cvals = cdist.cpu().numpy()
+    log("mix kernel: avg %.3f ms (min %.3f, max %.3f) -> %.1f GB/s algorithmic, %.1f %% of %d GB/s"
+        % (mix_avg, min(mix_ms), max(mix_ms), achieved, 100 * achieved / HBM_PEAK_GBS, HBM_PEAK_GBS))
+    if not args.no_consensus:
+        cgb = 4 * n * d / (con_avg * 1e-3) / 1e9
+        log("consensus kernels: avg %.3f ms -> %.1f GB/s algorithmic (4 B/element), %.1f %% of peak"
+            % (con_avg, cgb, 100 * cgb / HBM_PEAK_GBS))
+        log("consensus distance after the timed steps: first %.6g last %.6g" % (cvals[W], cvals[-1]))
+    log("whole step: %.3f ms wall per step over %d steps" % (1e3 * wall / K, K))
+
+    result = {
+        "metric": "replica-param updates/s for the fused mix+SGD step (whole hot-path step: table build, "
+                  "mix+SGD kernel, consensus distance)",
+        "value": n * d * K / wall,
+        "unit": "updates/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": 1e3 * wall / K,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": wl.name, "n": n, "d": d, "g_dtype": wl.g_dtype,
+            "topology": {0: "ring", 1: "rand_ring"}[wl.topology], "lr": wl.lr,
+            "delay_by_one": wl.delay, "consensus_every_step": not args.no_consensus,
+            "in_place": bool(args.in_place),
+        },
+        "roofline": {
+            "kernel": "mix_step_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
+            "algorithmic_bytes_per_launch": mix_bytes, "avg_launch_ms": mix_avg,
+        },
+        "mix_updates_per_s": n * d / (mix_avg * 1e-3),
+    }
+    if not args.no_consensus:
+        result["consensus"] = {"avg_ms": con_avg, "achieved_GBps": 4 * n * d / (con_avg * 1e-3) / 1e9,
+                               "frac": 4 * n * d / (con_avg * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    del X, Y, Gs
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl)
+        log("cpu baseline: %.3g updates/s on %d threads" % (result["cpu_baseline"]["value"],
+                                                            result["cpu_baseline"]["cores"]))
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()
