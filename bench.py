@@ -77,6 +77,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=5, help="1..5, the synthetic workload table")
     ap.add_argument("--no-consensus", action="store_true", help="leave the consensus distance out of the step")
+    ap.add_argument("--unfused", action="store_true",
+                    help="separate mix and consensus kernels instead of the fused psgd_mix_step_cd")
     ap.add_argument("--in-place", action="store_true", help="mix in place instead of ping-pong buffers")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -134,10 +136,12 @@ def main():
         G = Gs[k % 2]
         if wl.delay:
             psgd.synth_grad(X_prev, noise, G, wl.grad_pull, stream=stream)
+        fused = not (args.unfused or args.no_consensus)
         ev0[k].record(stream)
-        psgd.mix_step(X, Y, G, nbr_dev[k], w_dev[k], wl.lr, delay_mode=1 if wl.delay else 0, stream=stream)
+        psgd.mix_step(X, Y, G, nbr_dev[k], w_dev[k], wl.lr, delay_mode=1 if wl.delay else 0, stream=stream,
+                      cdist_out=cdist[k:k + 1] if fused else None)
         ev1[k].record(stream)
-        if not args.no_consensus:
+        if not (fused or args.no_consensus):
             psgd.consensus_dist_async(Y, cdist[k:k + 1], stream=stream)
         ev2[k].record(stream)
         if wl.delay:
@@ -169,7 +173,11 @@ def main():
     cvals = cdist.cpu().numpy()
     log("mix kernel: avg %.3f ms (min %.3f, max %.3f) -> %.1f GB/s algorithmic, %.1f %% of %d GB/s"
         % (mix_avg, min(mix_ms), max(mix_ms), achieved, 100 * achieved / HBM_PEAK_GBS, HBM_PEAK_GBS))
-    if not args.no_consensus:
+    fused = not (args.unfused or args.no_consensus)
+    if fused:
+        log("consensus distance is fused into the mix kernel; final reduce kernel avg %.4f ms" % con_avg)
+        log("consensus distance after the timed steps: first %.6g last %.6g" % (cvals[W], cvals[-1]))
+    elif not args.no_consensus:
         cgb = 4 * n * d / (con_avg * 1e-3) / 1e9
         log("consensus kernels: avg %.3f ms -> %.1f GB/s algorithmic (4 B/element), %.1f %% of peak"
             % (con_avg, cgb, 100 * cgb / HBM_PEAK_GBS))
@@ -194,17 +202,19 @@ def main():
             "workload": wl.name, "n": n, "d": d, "g_dtype": wl.g_dtype,
             "topology": {0: "ring", 1: "rand_ring"}[wl.topology], "lr": wl.lr,
             "delay_by_one": wl.delay, "consensus_every_step": not args.no_consensus,
+            "consensus_fused_into_mix_kernel": fused,
             "in_place": bool(args.in_place),
         },
         "roofline": {
-            "kernel": "mix_step_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+            "kernel": "mix_step_kernel (with fused consensus statistics)" if fused else "mix_step_kernel",
+            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
             "algorithmic_bytes_per_launch": mix_bytes, "avg_launch_ms": mix_avg,
         },
         "mix_updates_per_s": n * d / (mix_avg * 1e-3),
     }
-    if not args.no_consensus:
+    if not (args.no_consensus or fused):
         result["consensus"] = {"avg_ms": con_avg, "achieved_GBps": 4 * n * d / (con_avg * 1e-3) / 1e9,
                                "frac": 4 * n * d / (con_avg * 1e-3) / 1e9 / HBM_PEAK_GBS}
     del X, Y, Gs

@@ -111,6 +111,28 @@ int psgd_mix_step_bf16g(const float* X, float* X_out, const uint16_t* G_bf16,
                         int n, int64_t d, float lr, int delay_mode, void* stream);
 
 /*
+ * psgd_mix_step_cd / psgd_mix_step_cd_bf16g - the same fused step (Sec. 2, Eq. 2) that also
+ * returns the consensus distance of its own output, sum_i || x_out_i - mean(x_out) ||^2 (the
+ * quantity Sec. 3 bounds), without reading X_out back: the lane that produces all n rows of
+ * a column group keeps their running sums.  X_out is bit-identical to psgd_mix_step's.
+ *
+ *   cdist_out  device, double[1], 8-byte aligned, written by work enqueued on `stream`; it
+ *              must not overlap X, X_out or G.  NaN if the table held an out-of-range entry.
+ * The per-column sums are taken against the column's first output in fp64 and the
+ * per-workgroup partials are combined in a fixed order (bit-reproducible; it agrees with
+ * psgd_consensus_dist of X_out to rounding, about 1e-13 relative, not bit for bit).
+ * Uses the same per-device scratch as psgd_consensus_dist_async, so the same rule holds:
+ * calls that may overlap in time on one device must be serialised by the caller.
+ * All other arguments, modes and errors are those of psgd_mix_step; d = 0 writes 0.
+ */
+int psgd_mix_step_cd(const float* X, float* X_out, const float* G,
+                     const int32_t* nbr, const float* w,
+                     int n, int64_t d, float lr, int delay_mode, double* cdist_out, void* stream);
+int psgd_mix_step_cd_bf16g(const float* X, float* X_out, const uint16_t* G_bf16,
+                           const int32_t* nbr, const float* w,
+                           int n, int64_t d, float lr, int delay_mode, double* cdist_out, void* stream);
+
+/*
  * psgd_consensus_dist - sum_i || x_i - xbar ||^2 with xbar the mean of the n rows of X:
  * the distance from consensus whose decay Sec. 3 (Eqs. 5, 11, 12) bounds.
  *

@@ -30,6 +30,7 @@ constexpr int kThreads = 256;        // 4 wavefronts of 64 lanes
 constexpr int kTileBytes = 32 * 1024;  // LDS budget of the tiled path per workgroup
 constexpr int kUnroll = 8;           // rows whose loads are in flight together per lane
 constexpr int kMaxGrid = 4096;       // upper bound on persistent workgroups (scratch sizing)
+constexpr int kGridPerCu = 4;        // persistent workgroups per compute unit (16 waves per CU)
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -186,123 +187,6 @@ __device__ int stage_table(const int32_t* __restrict__ nbr, const float* __restr
 }
 
 // ---------------------------------------------------------------------------------------
-// Ring walk: one lane, one column group, all n rows, registers only.
-// Rows are visited in ring order p = 0..n-1.  `first` and `last` (positions 0 and n-1) stay
-// in registers for the wrap-around, so every X element is loaded exactly once and, when
-// X_out aliases X, always before the store that replaces it.
-// ---------------------------------------------------------------------------------------
-template <int VEC, typename GT>
-__device__ __forceinline__ void ring_walk(const float* xc, float* oc, const GT* __restrict__ gc,
-                                          const RingEnt* ring, int n, int64_t d, float neg_lr) {
-    typedef typename Cols<VEC>::T V;
-    const Cols<VEC> tag{};
-    const V first = ld_x(xc + (int64_t)ring_row(ring) * d, tag);
-    const V last = (n > 1) ? ld_x(xc + (int64_t)ring_row(ring + n - 1) * d, tag) : first;
-    V prev = last, cur = first;
-    int p = 0;
-    // Whole batches: positions p .. p+U-1, whose right neighbours p+1 .. p+U are all fresh
-    // loads (none of them is position n-1 or the wrap to position 0).
-    for (; p + kUnroll <= n - 2; p += kUnroll) {
-        RingEnt e[kUnroll];
-        V xs[kUnroll], gs[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            e[u] = ring_ent(ring + p + u);
-            xs[u] = ld_x(xc + (int64_t)ring_row(ring + p + u + 1) * d, tag);
-            gs[u] = ld_g(gc + (int64_t)e[u].row * d, tag);
-        }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            st_x(oc + (int64_t)e[u].row * d, mix_one<V>(e[u].w0, e[u].w1, e[u].w2, cur, prev, xs[u], gs[u], neg_lr));
-            prev = cur;
-            cur = xs[u];
-        }
-    }
-    // Remainder (at most U + 1 positions), with the wrap-around served from registers.
-    while (p < n) {
-        RingEnt e[kUnroll];
-        V xs[kUnroll], gs[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int pp = p + u;
-            if (pp < n) {
-                e[u] = ring_ent(ring + pp);
-                gs[u] = ld_g(gc + (int64_t)e[u].row * d, tag);
-                if (pp + 1 <= n - 2) xs[u] = ld_x(xc + (int64_t)ring_row(ring + pp + 1) * d, tag);
-                else if (pp + 1 == n - 1) xs[u] = last;
-                else xs[u] = first;
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            if (p + u < n) {
-                st_x(oc + (int64_t)e[u].row * d, mix_one<V>(e[u].w0, e[u].w1, e[u].w2, cur, prev, xs[u], gs[u], neg_lr));
-                prev = cur;
-                cur = xs[u];
-            }
-        }
-        p += kUnroll;
-    }
-}
-
-// ---------------------------------------------------------------------------------------
-// Tiled path for tables that are not a single ring.  The workgroup's 256 lanes form
-// (256 / lpr) row groups of lpr lanes; a tile is n rows by lpr column groups.
-// ---------------------------------------------------------------------------------------
-template <int VEC, typename GT>
-__device__ void tile_path(const float* X, float* Xout, const GT* __restrict__ G, const Lds& l,
-                          int n, int64_t d, int64_t ncg, float neg_lr, int lpr) {
-    typedef typename Cols<VEC>::T V;
-    const Cols<VEC> tag{};
-    V* tile = reinterpret_cast<V*>(l.scratch);
-    const int lane = threadIdx.x % lpr, rg = threadIdx.x / lpr, nrg = kThreads / lpr;
-    const int64_t ntiles = (ncg + lpr - 1) / lpr;
-    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
-        const int64_t cg = t * lpr + lane;
-        const bool active = cg < ncg;
-        const int64_t col = cg * VEC;
-        if (active)
-            for (int r = rg; r < n; r += nrg) tile[r * lpr + lane] = ld_x(X + (int64_t)r * d + col, tag);
-        __syncthreads();
-        if (active)
-            for (int r = rg; r < n; r += nrg) {
-                const V self = tile[l.nbr[3 * r] * lpr + lane];
-                const V left = tile[l.nbr[3 * r + 1] * lpr + lane];
-                const V right = tile[l.nbr[3 * r + 2] * lpr + lane];
-                const V g = ld_g(G + (int64_t)r * d + col, tag);
-                st_x(Xout + (int64_t)r * d + col,
-                     mix_one<V>(l.w[3 * r], l.w[3 * r + 1], l.w[3 * r + 2], self, left, right, g, neg_lr));
-            }
-        __syncthreads();
-    }
-}
-
-template <int VEC, typename GT>
-__global__ __launch_bounds__(kThreads) void mix_step_kernel(const float* X, float* Xout,
-                                                            const GT* __restrict__ G,
-                                                            const int32_t* __restrict__ nbr,
-                                                            const float* __restrict__ w, int n, int64_t d,
-                                                            float neg_lr, int lpr) {
-    extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-    const Lds l = carve(lds_raw, n);
-    const int kind = stage_table(nbr, w, n, l);
-    if (kind == kTableBad) {
-        if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&g_status_word, 1);
-        return;
-    }
-    const int64_t ncg = d / VEC;  // the launcher picks VEC = 1 unless 4 divides d
-    if (kind == kTableRing) {
-        const int64_t stride = (int64_t)gridDim.x * kThreads;
-        for (int64_t cg = (int64_t)blockIdx.x * kThreads + threadIdx.x; cg < ncg; cg += stride) {
-            const int64_t col = cg * VEC;
-            ring_walk<VEC, GT>(X + col, Xout + col, G + col, l.ring, n, d, neg_lr);
-        }
-    } else {
-        tile_path<VEC, GT>(X, Xout, G, l, n, d, ncg, neg_lr, lpr);
-    }
-}
-
-// ---------------------------------------------------------------------------------------
 // Consensus distance.  Per column: with pivot s = X[0, j],
 //   sum_i (x_i - xbar)^2 = sum_i (x_i - s)^2 - (sum_i (x_i - s))^2 / n,
 // one pass, differences and sums in fp64 (the difference of two fp32 values is exact in
@@ -348,6 +232,215 @@ __device__ __forceinline__ void pivot_of(f32x4 x, double* s) {
     for (int k = 0; k < 4; ++k) s[k] = (double)x[k];
 }
 
+// Running sums of one lane's column group; the first value it is given becomes the pivot.
+template <int VEC>
+struct ColStats {
+    double s[VEC], a[VEC], b[VEC];
+    int have;
+    __device__ __forceinline__ void reset() {
+        have = 0;
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) a[k] = b[k] = 0.0;
+    }
+    __device__ __forceinline__ void add(typename Cols<VEC>::T x) {
+        if (!have) {
+            pivot_of(x, s);
+            have = 1;
+        } else {
+            acc_diff<VEC>(a, b, x, s);
+        }
+    }
+    __device__ __forceinline__ double result(double inv_n) const {
+        double t = 0.0;
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) t += b[k] - a[k] * a[k] * inv_n;
+        return t;
+    }
+};
+
+// ---------------------------------------------------------------------------------------
+// Ring walk: one lane, one column group, all n rows, registers only.
+// Rows are visited in ring order p = 0..n-1.  `first` and `last` (positions 0 and n-1) stay
+// in registers for the wrap-around, so every X element is loaded exactly once and, when
+// X_out aliases X, always before the store that replaces it.
+// ---------------------------------------------------------------------------------------
+template <int VEC, typename GT, bool CD>
+__device__ __forceinline__ void ring_walk(const float* xc, float* oc, const GT* __restrict__ gc,
+                                          const RingEnt* ring, int n, int64_t d, float neg_lr,
+                                          ColStats<VEC>& stats) {
+    typedef typename Cols<VEC>::T V;
+    const Cols<VEC> tag{};
+    const V first = ld_x(xc + (int64_t)ring_row(ring) * d, tag);
+    const V last = (n > 1) ? ld_x(xc + (int64_t)ring_row(ring + n - 1) * d, tag) : first;
+    V prev = last, cur = first;
+    int p = 0;
+    // Whole batches: positions p .. p+U-1, whose right neighbours p+1 .. p+U are all fresh
+    // loads (none of them is position n-1 or the wrap to position 0).
+    for (; p + kUnroll <= n - 2; p += kUnroll) {
+        RingEnt e[kUnroll];
+        V xs[kUnroll], gs[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            e[u] = ring_ent(ring + p + u);
+            xs[u] = ld_x(xc + (int64_t)ring_row(ring + p + u + 1) * d, tag);
+            gs[u] = ld_g(gc + (int64_t)e[u].row * d, tag);
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const V out = mix_one<V>(e[u].w0, e[u].w1, e[u].w2, cur, prev, xs[u], gs[u], neg_lr);
+            st_x(oc + (int64_t)e[u].row * d, out);
+            if (CD) stats.add(out);
+            prev = cur;
+            cur = xs[u];
+        }
+    }
+    // Remainder (at most U + 1 positions), with the wrap-around served from registers.
+    while (p < n) {
+        RingEnt e[kUnroll];
+        V xs[kUnroll], gs[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int pp = p + u;
+            if (pp < n) {
+                e[u] = ring_ent(ring + pp);
+                gs[u] = ld_g(gc + (int64_t)e[u].row * d, tag);
+                if (pp + 1 <= n - 2) xs[u] = ld_x(xc + (int64_t)ring_row(ring + pp + 1) * d, tag);
+                else if (pp + 1 == n - 1) xs[u] = last;
+                else xs[u] = first;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            if (p + u < n) {
+                const V out = mix_one<V>(e[u].w0, e[u].w1, e[u].w2, cur, prev, xs[u], gs[u], neg_lr);
+                st_x(oc + (int64_t)e[u].row * d, out);
+                if (CD) stats.add(out);
+                prev = cur;
+                cur = xs[u];
+            }
+        }
+        p += kUnroll;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Tiled path for tables that are not a single ring.  The workgroup's 256 lanes form
+// (256 / lpr) row groups of lpr lanes; a tile is n rows by lpr column groups.
+// ---------------------------------------------------------------------------------------
+// Extra LDS of the tiled path when it also gathers the consensus statistics: one pivot per
+// column group and one (a, b) pair per lane for the combine across row groups.
+__host__ __device__ inline size_t tile_cd_bytes(int lpr, int vec) {
+    return (size_t)lpr * vec * sizeof(float) + 8 + (size_t)kThreads * 2 * vec * sizeof(double);
+}
+
+template <int VEC, typename GT, bool CD>
+__device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ G, const Lds& l,
+                            int n, int64_t d, int64_t ncg, float neg_lr, int lpr, double inv_n) {
+    typedef typename Cols<VEC>::T V;
+    const Cols<VEC> tag{};
+    V* tile = reinterpret_cast<V*>(l.scratch);
+    V* pivot = tile + (size_t)n * lpr;                          // [lpr]            (CD only)
+    double* comb = reinterpret_cast<double*>((reinterpret_cast<uintptr_t>(pivot + lpr) + 7) & ~(uintptr_t)7);  // [256][2 * VEC]
+    const int lane = threadIdx.x % lpr, rg = threadIdx.x / lpr, nrg = kThreads / lpr;
+    const int64_t ntiles = (ncg + lpr - 1) / lpr;
+    double total = 0.0;
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const int64_t cg = t * lpr + lane;
+        const bool active = cg < ncg;
+        const int64_t col = cg * VEC;
+        if (active)
+            for (int r = rg; r < n; r += nrg) tile[r * lpr + lane] = ld_x(X + (int64_t)r * d + col, tag);
+        __syncthreads();
+        if (active)
+            for (int r = rg; r < n; r += nrg) {
+                const V self = tile[l.nbr[3 * r] * lpr + lane];
+                const V left = tile[l.nbr[3 * r + 1] * lpr + lane];
+                const V right = tile[l.nbr[3 * r + 2] * lpr + lane];
+                const V g = ld_g(G + (int64_t)r * d + col, tag);
+                const V out = mix_one<V>(l.w[3 * r], l.w[3 * r + 1], l.w[3 * r + 2], self, left, right, g, neg_lr);
+                st_x(Xout + (int64_t)r * d + col, out);
+                if (CD && r == 0) pivot[lane] = out;
+            }
+        __syncthreads();
+        if (CD) {
+            // Second sweep over the intact tile: the same outputs again (G is read-only, so
+            // re-reading it is safe even when X_out aliases X), now measured against the
+            // column's pivot, then summed over the row groups in a fixed order.
+            double s[VEC], a[VEC], b[VEC];
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) a[k] = b[k] = 0.0;
+            if (active) {
+                pivot_of(pivot[lane], s);
+                for (int r = rg; r < n; r += nrg) {
+                    if (r == 0) continue;
+                    const V self = tile[l.nbr[3 * r] * lpr + lane];
+                    const V left = tile[l.nbr[3 * r + 1] * lpr + lane];
+                    const V right = tile[l.nbr[3 * r + 2] * lpr + lane];
+                    const V g = ld_g(G + (int64_t)r * d + col, tag);
+                    acc_diff<VEC>(a, b, mix_one<V>(l.w[3 * r], l.w[3 * r + 1], l.w[3 * r + 2], self, left, right, g, neg_lr), s);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) {
+                comb[(size_t)threadIdx.x * 2 * VEC + k] = a[k];
+                comb[(size_t)threadIdx.x * 2 * VEC + VEC + k] = b[k];
+            }
+            __syncthreads();
+            if (active && rg == 0) {
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) {
+                    double at = 0.0, bt = 0.0;
+                    for (int q = 0; q < nrg; ++q) {
+                        at += comb[(size_t)(q * lpr + lane) * 2 * VEC + k];
+                        bt += comb[(size_t)(q * lpr + lane) * 2 * VEC + VEC + k];
+                    }
+                    total += bt - at * at * inv_n;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    return total;
+}
+
+// CD = also reduce the consensus distance of the outputs into partials[blockIdx.x].
+template <int VEC, typename GT, bool CD>
+__global__ __launch_bounds__(kThreads) void mix_step_kernel(const float* X, float* Xout,
+                                                            const GT* __restrict__ G,
+                                                            const int32_t* __restrict__ nbr,
+                                                            const float* __restrict__ w, int n, int64_t d,
+                                                            float neg_lr, int lpr, double* __restrict__ partials) {
+    extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+    __shared__ double lds4[4];
+    const Lds l = carve(lds_raw, n);
+    const int kind = stage_table(nbr, w, n, l);
+    if (kind == kTableBad) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&g_status_word, 1);
+        if (CD && threadIdx.x == 0) partials[blockIdx.x] = __builtin_nan("");
+        return;
+    }
+    const int64_t ncg = d / VEC;  // the launcher picks VEC = 1 unless 4 divides d
+    const double inv_n = 1.0 / (double)n;
+    double total = 0.0;
+    if (kind == kTableRing) {
+        const int64_t stride = (int64_t)gridDim.x * kThreads;
+        for (int64_t cg = (int64_t)blockIdx.x * kThreads + threadIdx.x; cg < ncg; cg += stride) {
+            const int64_t col = cg * VEC;
+            ColStats<VEC> stats;
+            if (CD) stats.reset();
+            ring_walk<VEC, GT, CD>(X + col, Xout + col, G + col, l.ring, n, d, neg_lr, stats);
+            if (CD) total += stats.result(inv_n);
+        }
+    } else {
+        total = tile_path<VEC, GT, CD>(X, Xout, G, l, n, d, ncg, neg_lr, lpr, inv_n);
+    }
+    if (CD) {
+        const double bs = block_sum(total, lds4);
+        if (threadIdx.x == 0) partials[blockIdx.x] = bs;
+    }
+}
+
+// Consensus-distance kernels (the per-column arithmetic is defined above the ring walk).
 template <int VEC>
 __global__ __launch_bounds__(kThreads) void consensus_partial_kernel(const float* __restrict__ X, int n,
                                                                      int64_t d, double* __restrict__ partials) {
@@ -470,16 +563,45 @@ inline int persistent_grid(const DeviceInfo& di, int64_t work_items, int per_cu)
     return (int)(g < 1 ? 1 : g);
 }
 
+// Launches one instantiation of the mix kernel on a persistent grid sized to what is
+// actually resident: min(kGridPerCu, occupancy for this LDS size) workgroups per CU.
+// Returns the grid size.  The occupancy query is cached per instantiation and LDS size.
+template <int VEC, typename GT, bool CD>
+int launch_mix(const DeviceInfo& di, size_t lds_bytes, hipStream_t s, const float* X, float* X_out, const GT* G,
+               const int32_t* nbr, const float* w, int n, int64_t d, float neg_lr, int lpr, double* partials) {
+    static std::mutex mu;
+    static size_t cached_lds = ~(size_t)0;
+    static int cached_occ = 0;
+    int occ = 0;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        if (cached_lds != lds_bytes) {
+            int q = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&q, mix_step_kernel<VEC, GT, CD>, kThreads, lds_bytes) !=
+                    hipSuccess || q < 1)
+                q = 1;
+            cached_occ = q;
+            cached_lds = lds_bytes;
+        }
+        occ = cached_occ;
+    }
+    const int per_cu = occ < kGridPerCu ? occ : kGridPerCu;
+    const int grid = persistent_grid(di, d / VEC, per_cu);
+    hipLaunchKernelGGL((mix_step_kernel<VEC, GT, CD>), dim3(grid), dim3(kThreads), lds_bytes, s, X, X_out, G, nbr, w, n,
+                       d, neg_lr, lpr, partials);
+    return grid;
+}
+
 template <typename GT>
 int mix_step_impl(const char* name, const float* X, float* X_out, const GT* G, const int32_t* nbr, const float* w,
-                  int n, int64_t d, float lr, int delay_mode, void* stream) {
+                  int n, int64_t d, float lr, int delay_mode, bool want_cd, double* cd_out, void* stream) {
     clear_error();
-    if (!X || !X_out || !G || !nbr || !w) return fail(PSGD_EINVAL, "%s: null pointer", name);
+    if (!X || !X_out || !G || !nbr || !w || (want_cd && !cd_out)) return fail(PSGD_EINVAL, "%s: null pointer", name);
     if (n < 1 || n > PSGD_MAX_N) return fail(PSGD_EINVAL, "%s: n=%d outside 1..%d", name, n, (int)PSGD_MAX_N);
     if (d < 0) return fail(PSGD_EINVAL, "%s: d=%lld is negative", name, (long long)d);
     if (delay_mode != 0 && delay_mode != 1) return fail(PSGD_EINVAL, "%s: delay_mode=%d", name, delay_mode);
     if (!aligned_to(X, 4) || !aligned_to(X_out, 4) || !aligned_to(G, sizeof(GT)) || !aligned_to(nbr, 4) ||
-        !aligned_to(w, 4))
+        !aligned_to(w, 4) || (want_cd && !aligned_to(cd_out, 8)))
         return fail(PSGD_EALIGN, "%s: pointer not aligned to its element size", name);
     if (d > 0 && (int64_t)n > INT64_MAX / 4 / d) return fail(PSGD_EINVAL, "%s: n*d overflows", name);
     const size_t xbytes = (size_t)n * (size_t)d * sizeof(float), gbytes = (size_t)n * (size_t)d * sizeof(GT);
@@ -490,32 +612,49 @@ int mix_step_impl(const char* name, const float* X, float* X_out, const GT* G, c
         return fail(PSGD_EALIAS, "%s: X_out partially overlaps X", name);
     }
     if (overlaps(G, gbytes, X_out, xbytes)) return fail(PSGD_EALIAS, "%s: X_out overlaps G", name);
-    if (d == 0) return PSGD_OK;
-
+    if (want_cd && (overlaps(cd_out, 8, X_out, xbytes) || overlaps(cd_out, 8, X, xbytes) || overlaps(cd_out, 8, G, gbytes)))
+        return fail(PSGD_EALIAS, "%s: the distance output overlaps a data buffer", name);
+    hipStream_t s = static_cast<hipStream_t>(stream);
     DeviceInfo* di = nullptr;
-    if (int rc = device_info(&di, false)) return rc;
+    if (d == 0) {
+        if (!want_cd) return PSGD_OK;
+        if (int rc = device_info(&di, true)) return rc;
+        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, di->scratch, 0, cd_out);
+        const hipError_t e0 = hipGetLastError();
+        return e0 == hipSuccess ? PSGD_OK : hip_fail(e0, "consensus_final_kernel");
+    }
+    if (int rc = device_info(&di, want_cd)) return rc;
 
     // 128-bit path needs every row start 16-byte aligned (8-byte for bf16 gradients).
     const bool vec4 = (d % 4 == 0) && aligned_to(X, 16) && aligned_to(X_out, 16) && aligned_to(G, 4 * sizeof(GT));
     const int vec = vec4 ? 4 : 1;
     // Tile shape of the fallback path: widest power-of-two lane count whose tile fits.
+    const size_t tile_budget = want_cd ? (size_t)kTileBytes / 2 : (size_t)kTileBytes;
     int lpr = 64;
-    while (lpr > 1 && (size_t)n * lpr * vec * sizeof(float) > (size_t)kTileBytes) lpr >>= 1;
-    size_t scratch_bytes = (size_t)n * lpr * vec * sizeof(float);
+    while (lpr > 1 && (size_t)n * lpr * vec * sizeof(float) > tile_budget) lpr >>= 1;
+    size_t scratch_bytes = (size_t)n * lpr * vec * sizeof(float) + (want_cd ? tile_cd_bytes(lpr, vec) : 0);
     if (scratch_bytes < (size_t)n * 4 * sizeof(int)) scratch_bytes = (size_t)n * 4 * sizeof(int);
     const size_t lds_bytes = ((lds_table_bytes(n) + 15) & ~(size_t)15) + scratch_bytes;
-    if (lds_bytes > 64 * 1024) return fail(PSGD_EINVAL, "%s: n=%d needs %zu bytes of LDS", name, n, lds_bytes);
+    if (lds_bytes > 64 * 1024 - 64) return fail(PSGD_EINVAL, "%s: n=%d needs %zu bytes of LDS", name, n, lds_bytes);
 
-    const int grid = persistent_grid(*di, d / vec, 8);
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    if (vec4)
-        hipLaunchKernelGGL((mix_step_kernel<4, GT>), dim3(grid), dim3(kThreads), lds_bytes, s, X, X_out, G, nbr, w, n,
-                           d, -lr, lpr);
+    const float neg_lr = -lr;
+    double* partials = want_cd ? di->scratch : nullptr;
+    int grid = 0;
+    if (vec4 && want_cd)
+        grid = launch_mix<4, GT, true>(*di, lds_bytes, s, X, X_out, G, nbr, w, n, d, neg_lr, lpr, partials);
+    else if (vec4)
+        grid = launch_mix<4, GT, false>(*di, lds_bytes, s, X, X_out, G, nbr, w, n, d, neg_lr, lpr, partials);
+    else if (want_cd)
+        grid = launch_mix<1, GT, true>(*di, lds_bytes, s, X, X_out, G, nbr, w, n, d, neg_lr, lpr, partials);
     else
-        hipLaunchKernelGGL((mix_step_kernel<1, GT>), dim3(grid), dim3(kThreads), lds_bytes, s, X, X_out, G, nbr, w, n,
-                           d, -lr, lpr);
-    const hipError_t e = hipGetLastError();
+        grid = launch_mix<1, GT, false>(*di, lds_bytes, s, X, X_out, G, nbr, w, n, d, neg_lr, lpr, partials);
+    hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, name);
+    if (want_cd) {
+        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, partials, grid, cd_out);
+        e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e, "consensus_final_kernel");
+    }
     return PSGD_OK;
 }
 
@@ -523,7 +662,7 @@ int consensus_enqueue(const float* X, int n, int64_t d, double* out_dev, hipStre
     DeviceInfo* di = nullptr;
     if (int rc = device_info(&di, true)) return rc;
     const bool vec4 = (d % 4 == 0) && aligned_to(X, 16);
-    const int grid = persistent_grid(*di, vec4 ? d / 4 : d, 8);
+    const int grid = persistent_grid(*di, vec4 ? d / 4 : d, 8);  // light kernel: 32 waves per CU
     if (vec4)
         hipLaunchKernelGGL(consensus_partial_kernel<4>, dim3(grid), dim3(kThreads), 0, s, X, n, d, di->scratch);
     else
@@ -553,13 +692,26 @@ extern "C" {
 
 int psgd_mix_step(const float* X, float* X_out, const float* G, const int32_t* nbr, const float* w, int n, int64_t d,
                   float lr, int delay_mode, void* stream) {
-    return psgd::mix_step_impl<float>("psgd_mix_step", X, X_out, G, nbr, w, n, d, lr, delay_mode, stream);
+    return psgd::mix_step_impl<float>("psgd_mix_step", X, X_out, G, nbr, w, n, d, lr, delay_mode, false, nullptr,
+                                      stream);
 }
 
 int psgd_mix_step_bf16g(const float* X, float* X_out, const uint16_t* G_bf16, const int32_t* nbr, const float* w,
                         int n, int64_t d, float lr, int delay_mode, void* stream) {
-    return psgd::mix_step_impl<uint16_t>("psgd_mix_step_bf16g", X, X_out, G_bf16, nbr, w, n, d, lr, delay_mode,
-                                         stream);
+    return psgd::mix_step_impl<uint16_t>("psgd_mix_step_bf16g", X, X_out, G_bf16, nbr, w, n, d, lr, delay_mode, false,
+                                         nullptr, stream);
+}
+
+int psgd_mix_step_cd(const float* X, float* X_out, const float* G, const int32_t* nbr, const float* w, int n,
+                     int64_t d, float lr, int delay_mode, double* cdist_out, void* stream) {
+    return psgd::mix_step_impl<float>("psgd_mix_step_cd", X, X_out, G, nbr, w, n, d, lr, delay_mode, true, cdist_out,
+                                      stream);
+}
+
+int psgd_mix_step_cd_bf16g(const float* X, float* X_out, const uint16_t* G_bf16, const int32_t* nbr, const float* w,
+                           int n, int64_t d, float lr, int delay_mode, double* cdist_out, void* stream) {
+    return psgd::mix_step_impl<uint16_t>("psgd_mix_step_cd_bf16g", X, X_out, G_bf16, nbr, w, n, d, lr, delay_mode,
+                                         true, cdist_out, stream);
 }
 
 double psgd_consensus_dist(const float* X, int n, int64_t d) {

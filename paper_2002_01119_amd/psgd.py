@@ -21,7 +21,8 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libpsgd.so
 _lib = None
 
 EXPORTS = (
-    "psgd_build_mixing", "psgd_mix_step", "psgd_mix_step_bf16g", "psgd_consensus_dist",
+    "psgd_build_mixing", "psgd_mix_step", "psgd_mix_step_bf16g", "psgd_mix_step_cd",
+    "psgd_mix_step_cd_bf16g", "psgd_consensus_dist",
     "psgd_consensus_dist_async", "psgd_synth_grad", "psgd_device_status", "psgd_last_error",
     "psgd_version",
 )
@@ -53,6 +54,11 @@ def load(reload=False):
         fn.restype = ctypes.c_int
         fn.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int, ctypes.c_int64, ctypes.c_float,
                        ctypes.c_int, vp]
+    for name in ("psgd_mix_step_cd", "psgd_mix_step_cd_bf16g"):
+        fn = getattr(lib, name)
+        fn.restype = ctypes.c_int
+        fn.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int, ctypes.c_int64, ctypes.c_float,
+                       ctypes.c_int, vp, vp]
     lib.psgd_consensus_dist.restype = ctypes.c_double
     lib.psgd_consensus_dist.argtypes = [vp, ctypes.c_int, ctypes.c_int64]
     lib.psgd_consensus_dist_async.restype = ctypes.c_int
@@ -102,9 +108,11 @@ def build_mixing(topology, n, seed=0, step=0):
     return nbr, w
 
 
-def mix_step(X, X_out, G, nbr, w, lr, delay_mode=0, stream=None):
+def mix_step(X, X_out, G, nbr, w, lr, delay_mode=0, stream=None, cdist_out=None):
     """Enqueue X_out = mix(X) - lr * G.  All arguments are device tensors; G is float32, or
-    bfloat16 / int16 / uint16 (bf16 bit patterns), which selects psgd_mix_step_bf16g."""
+    bfloat16 / int16 / uint16 (bf16 bit patterns), which selects the *_bf16g entry point.
+    With cdist_out (device float64 tensor, >= 1 element) the fused psgd_mix_step_cd variant
+    also writes the consensus distance of X_out there."""
     import torch
     n, d = _rows_cols(X)
     if tuple(X_out.shape) != (n, d) or tuple(G.shape) != (n, d) or not X_out.is_contiguous() \
@@ -120,13 +128,21 @@ def mix_step(X, X_out, G, nbr, w, lr, delay_mode=0, stream=None):
             raise ValueError("all tensors must live on one device")
     lib = load()
     if G.dtype == torch.float32:
-        fn = lib.psgd_mix_step
+        bf16 = False
     elif G.dtype in (torch.bfloat16, torch.int16, torch.uint16):
-        fn = lib.psgd_mix_step_bf16g
+        bf16 = True
     else:
         raise ValueError("G must be float32 or bfloat16 bit patterns")
-    _check(fn(X.data_ptr(), X_out.data_ptr(), G.data_ptr(), nbr.data_ptr(), w.data_ptr(), n, d,
-              float(lr), int(delay_mode), _stream_handle(stream)))
+    if cdist_out is None:
+        fn = lib.psgd_mix_step_bf16g if bf16 else lib.psgd_mix_step
+        _check(fn(X.data_ptr(), X_out.data_ptr(), G.data_ptr(), nbr.data_ptr(), w.data_ptr(), n, d,
+                  float(lr), int(delay_mode), _stream_handle(stream)))
+    else:
+        if cdist_out.dtype != torch.float64 or cdist_out.numel() < 1 or cdist_out.device != X.device:
+            raise ValueError("cdist_out must be a float64 device tensor")
+        fn = lib.psgd_mix_step_cd_bf16g if bf16 else lib.psgd_mix_step_cd
+        _check(fn(X.data_ptr(), X_out.data_ptr(), G.data_ptr(), nbr.data_ptr(), w.data_ptr(), n, d,
+                  float(lr), int(delay_mode), cdist_out.data_ptr(), _stream_handle(stream)))
 
 
 def consensus_dist(X):

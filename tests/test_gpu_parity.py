@@ -247,6 +247,80 @@ def test_consensus_is_reproducible(psgd):
     assert len(vals) == 1
 
 
+# ------------------------------------------------------------------------- fused step + distance
+def run_step_cd(psgd, X, G, nbr, w, lr, in_place=False):
+    Xd = dev(X)
+    Gd = bits_dev(G) if G.dtype == np.uint16 else dev(G)
+    out = Xd if in_place else torch.full_like(Xd, float("nan"))
+    c = torch.full((1,), float("nan"), dtype=torch.float64, device="cuda:0")
+    psgd.mix_step(Xd, out, Gd, dev(nbr), dev(w), lr, cdist_out=c)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), c.item()
+
+
+@pytest.mark.parametrize("n,d", SHAPES)
+@pytest.mark.parametrize("topo", [orc.TOPO_RING, orc.TOPO_RAND_RING])
+@pytest.mark.parametrize("gkind", ["f32", "bf16"])
+def test_fused_step_and_distance_match_oracle(psgd, n, d, topo, gkind):
+    X = inp.host_normal_f32((n, d), 1.0, 600 + n)
+    G = inp.host_normal_f32((n, d), 0.5, 700 + n)
+    if gkind == "bf16":
+        G = inp.f32_to_bf16_bits(G)
+    nbr, w = psgd.build_mixing(topo, n, seed=19, step=n + d)
+    want = orc.mix_step(X, G, orc.densify(nbr, w), 0.1)
+    got, c = run_step_cd(psgd, X, G, nbr, w, 0.1)
+    assert np.array_equal(got.view(np.uint32), run_step(psgd, X, G, nbr, w, 0.1).view(np.uint32))
+    assert_close(got, want)
+    # the distance is that of the fp32 array the kernel wrote
+    c_ref = orc.consensus_dist(got)
+    assert abs(c - c_ref) <= REL * c_ref + 1e-300
+    assert abs(c - orc.consensus_dist(want)) <= 1e-5 * c_ref + 1e-300
+    got_ip, c_ip = run_step_cd(psgd, X, G, nbr, w, 0.1, in_place=True)
+    assert np.array_equal(got_ip.view(np.uint32), got.view(np.uint32)) and c_ip == c
+
+
+@pytest.mark.parametrize("n,d", [(4, 9), (6, 2048), (16, 4 * 3000), (64, 1025), (128, 8192 + 4), (300, 516)])
+@pytest.mark.parametrize("gkind", ["f32", "bf16"])
+def test_fused_distance_on_general_tables(psgd, n, d, gkind):
+    rng = np.random.default_rng(n * 11 + d)
+    nbr, w = _general_table(n, rng)
+    X = inp.host_normal_f32((n, d), 1.0, 800 + n)
+    G = inp.host_normal_f32((n, d), 0.5, 900 + n)
+    if gkind == "bf16":
+        G = inp.f32_to_bf16_bits(G)
+    got, c = run_step_cd(psgd, X, G, nbr, w, 0.2)
+    assert_close(got, orc.mix_step(X, G, orc.densify(nbr, w), 0.2))
+    c_ref = orc.consensus_dist(got)
+    assert abs(c - c_ref) <= REL * c_ref
+    got_ip, c_ip = run_step_cd(psgd, X, G, nbr, w, 0.2, in_place=True)
+    assert np.array_equal(got_ip.view(np.uint32), got.view(np.uint32)) and c_ip == c
+
+
+def test_fused_distance_special_cases(psgd):
+    # outputs far from the origin and close together (large common gradient)
+    n, d = 16, 5000
+    X = np.tile(inp.host_normal_f32((1, d), 1.0, 1), (n, 1)) + inp.host_normal_f32((n, d), 1e-4, 2)
+    G = np.full((n, d), 1000.0, np.float32)
+    nbr, w = psgd.build_mixing(psgd.TOPO_RAND_RING, n, 1, 1)
+    got, c = run_step_cd(psgd, X.astype(np.float32), G, nbr, w, 1.0)
+    c_ref = orc.consensus_dist(got)
+    assert abs(c - c_ref) <= REL * c_ref
+    # invalid table: nothing written, distance NaN, flag raised
+    bad = nbr.copy()
+    bad[0, 1] = 99
+    got, c = run_step_cd(psgd, X.astype(np.float32), G, bad, w, 1.0)
+    assert np.isnan(got).all() and np.isnan(c) and psgd.device_status(clear=True) == 1
+    # zero columns: distance 0
+    bufs = [torch.zeros(16, device="cuda:0") for _ in range(3)]
+    cz = torch.full((1,), 5.0, dtype=torch.float64, device="cuda:0")
+    n4, w4 = psgd.build_mixing(psgd.TOPO_RING, 4)
+    n4d, w4d = dev(n4), dev(w4)
+    rc = psgd.load().psgd_mix_step_cd(bufs[0].data_ptr(), bufs[1].data_ptr(), bufs[2].data_ptr(), n4d.data_ptr(),
+                                      w4d.data_ptr(), 4, 0, 0.1, 0, cz.data_ptr(), None)
+    torch.cuda.synchronize()
+    assert rc == 0 and cz.item() == 0.0
+
+
 # ------------------------------------------------------------------------- gradient producer
 def test_synth_grad_matches_oracle(psgd):
     for count in (1, 5, 4096, 100_003):

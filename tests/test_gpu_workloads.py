@@ -111,6 +111,7 @@ def run_workload(psgd, wl, topo, steps=None):
     scale_hist, fro_hist = np.abs(Xo).max(), np.linalg.norm(Xo)
     cdist, Ts = [], []
     c_out = torch.zeros(steps, dtype=torch.float64, device="cuda:0")
+    c_chk = torch.zeros(1, dtype=torch.float64, device="cuda:0")
     for k in range(steps):
         nbr, w = psgd.build_mixing(topo, n, wl.seed_perm, k)
         T = orc.densify(nbr, w)
@@ -127,8 +128,16 @@ def run_workload(psgd, wl, topo, steps=None):
         else:
             G = inp.device_normal_f32((n, d), wl.sigma_g, wl.seed_g * 1000 + k)
             Go = pull(G, cols_t)
-        psgd.mix_step(X, Y, G, dev(nbr), dev(w), wl.lr, delay_mode=1 if wl.delay else 0)
-        psgd.consensus_dist_async(Y, c_out[k:k + 1])
+        if k % 2 == 0:      # alternate the fused entry point with the two separate calls
+            psgd.mix_step(X, Y, G, dev(nbr), dev(w), wl.lr, delay_mode=1 if wl.delay else 0,
+                          cdist_out=c_out[k:k + 1])
+            if k < 4:
+                psgd.consensus_dist_async(Y, c_chk)
+                torch.cuda.synchronize()
+                assert abs(c_out[k].item() - c_chk.item()) <= 1e-9 * c_chk.item()
+        else:
+            psgd.mix_step(X, Y, G, dev(nbr), dev(w), wl.lr, delay_mode=1 if wl.delay else 0)
+            psgd.consensus_dist_async(Y, c_out[k:k + 1])
         Xo_next = orc.mix_step(Xo, Go, T, wl.lr)
         Xo_prev, Xo = Xo, Xo_next
         if wl.delay:

@@ -19,7 +19,7 @@ def test_library_exports_every_declared_symbol():
     with open(os.path.join(ROOT, "include", "psgd.h")) as f:
         text = re.sub(r"/\*.*?\*/", "", f.read(), flags=re.S)
     declared = sorted(set(re.findall(r"\b(psgd_[a-z0-9_]+)\s*\(", text)))
-    assert len(declared) >= 9
+    assert len(declared) >= 11
     for name in declared:
         assert hasattr(lib, name), name
     assert sorted(psgd.EXPORTS) == declared
@@ -100,6 +100,10 @@ def test_mix_step_argument_checks_need_no_device():
     assert call(O=A + 16) == psgd.EALIAS and "partially" in psgd.last_error()
     assert call(O=A, mode=1) == psgd.EALIAS and "delay" in psgd.last_error()
     assert call(G=B + 4 * 100) == psgd.EALIAS
+    assert lib.psgd_mix_step_cd(A, B, C, T1, T2, n, d, 0.1, 0, None, None) == psgd.EINVAL
+    assert lib.psgd_mix_step_cd(A, B, C, T1, T2, n, d, 0.1, 0, 0x3000004, None) == psgd.EALIGN
+    assert lib.psgd_mix_step_cd(A, B, C, T1, T2, n, d, 0.1, 0, B + 8, None) == psgd.EALIAS
+    assert lib.psgd_mix_step_cd_bf16g(A, A, C, T1, T2, n, d, 0.1, 1, 0x3000000, None) == psgd.EALIAS
     # an empty model is a no-op that needs no device either; in-place is legal in mode 0
     assert call(d=0) == psgd.OK
     assert call(O=A, d=0) == psgd.OK
