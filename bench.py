@@ -23,10 +23,14 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per launch of the mix kernel on workload 5 from two rocprofv3 --pmc runs
-# (FETCH_SIZE, then WRITE_SIZE), each scaled by the same counter's reading for a plain copy
-# of known size; None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per launch of the (fused) mix kernel from two rocprofv3 --pmc runs (FETCH_SIZE,
+# then WRITE_SIZE, in KiB per dispatch), each scaled by the same counter's reading for a plain
+# device copy of known size (--calibrate-copy): FETCH_SIZE reads half the true bytes on this
+# chip (factor 2.000), WRITE_SIZE reads them all (factor 1.000).  Workloads not yet measured
+# report null.
+MEASURED_TRAFFIC_BYTES = {
+    "cfg5_n64_d100M_bf16g_randring": (18_750_600 * 2.000 + 25_000_000 * 1.000) * 1024,
+}
 
 
 def log(*a):
@@ -81,6 +85,10 @@ def main():
                     help="separate mix and consensus kernels instead of the fused psgd_mix_step_cd")
     ap.add_argument("--in-place", action="store_true", help="mix in place instead of ping-pong buffers")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="before the warm-up, run one plain device copy X -> X_out of known size (n*d*4 bytes read "
+                         "and written); under rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE readings calibrate the "
+                         "mix kernel's")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs all learners on ONE GPU (no collectives); --gpus %d is not "
@@ -150,6 +158,16 @@ def main():
             X, Y = Y, X
 
     with torch.cuda.stream(stream):
+        if args.calibrate_copy and not args.in_place:
+            Y.copy_(X)
+            t_c0, t_c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t_c0.record(stream)
+            Y.copy_(X)
+            t_c1.record(stream)
+            torch.cuda.synchronize()
+            cms = t_c0.elapsed_time(t_c1)
+            log("plain device copy X -> X_out: %.3f ms -> %.1f GB/s (%.1f %% of peak)"
+                % (cms, 8 * n * d / cms / 1e6, 8 * n * d / cms / 1e6 / HBM_PEAK_GBS * 100))
         for k in range(W):
             one_step(k)
         torch.cuda.synchronize()
