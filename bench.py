@@ -85,6 +85,9 @@ def main():
                     help="separate mix and consensus kernels instead of the fused psgd_mix_step_cd")
     ap.add_argument("--in-place", action="store_true", help="mix in place instead of ping-pong buffers")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-placement", action="store_true",
+                    help="allocate X / X_out as separate tensors instead of probing one HBM pool for the windows "
+                         "with the best write rate (see paper_2002_01119_amd/placement.py)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="before the warm-up, run one plain device copy X -> X_out of known size (n*d*4 bytes read "
                          "and written); under rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE readings calibrate the "
@@ -113,16 +116,42 @@ def main():
     log("workload %s: n=%d d=%d G=%s steps=%d warmup=%d" % (wl.name, n, d, wl.g_dtype, K, W))
 
     # ---- resident inputs
-    X = inp.device_normal_f32((n, d), wl.sigma_x, wl.seed_x, dev)
-    Y = X if args.in_place else torch.empty_like(X)
     if wl.g_dtype == "bf16":
         Gs = [inp.device_normal_bf16((n, d), wl.sigma_g, wl.seed_g + i, dev) for i in range(2)]
     else:
         Gs = [inp.device_normal_f32((n, d), wl.sigma_g, wl.seed_g + i, dev) for i in range(2)]
+    n_xbuf = 1 if args.in_place else (3 if wl.delay else 2)
+    placement, pool = None, None
+    if not args.no_placement:
+        # X and X_out are rewritten every step: put them where this chip writes fastest
+        from paper_2002_01119_amd import placement as plc
+        nbr0, w0 = psgd.build_mixing(wl.topology, n, wl.seed_perm, 0)
+        extra = (n * d * 4 if wl.delay else 0) + (6 << 30)          # noise buffer + headroom
+        try:
+            views, pool, placement = plc.place_replica_buffers(
+                n, d, n_xbuf, Gs[0], torch.from_numpy(nbr0).to(dev), torch.from_numpy(w0).to(dev),
+                reserve_bytes=extra, max_pool_bytes=12 * n * d * 4, log=log)
+        except (torch.OutOfMemoryError, RuntimeError) as e:
+            log("placement probe skipped (%s); falling back to separate allocations" % (str(e).splitlines()[0],))
+            views = None
+    else:
+        views = None
+    if views is not None:
+        X = views[0]
+        g = torch.Generator(device=dev)
+        g.manual_seed(wl.seed_x)
+        X.normal_(0.0, wl.sigma_x, generator=g)
+        Y = X if args.in_place else views[1]
+    else:
+        X = inp.device_normal_f32((n, d), wl.sigma_x, wl.seed_x, dev)
+        Y = X if args.in_place else torch.empty_like(X)
     noise = None
     if wl.delay:                      # delay-by-one: G_k = c * X_{k-1} + noise, three X buffers
         noise = inp.device_normal_f32((n, d), wl.sigma_g, wl.seed_g + 7, dev)
-    X_prev = X.clone() if wl.delay else None
+    X_prev = None
+    if wl.delay:
+        X_prev = views[2] if views is not None else torch.empty_like(X)
+        X_prev.copy_(X)
     nbr_host = torch.empty((total, n, 3), dtype=torch.int32, pin_memory=True)
     w_host = torch.empty((total, n, 3), dtype=torch.float32, pin_memory=True)
     nbr_dev = torch.empty((total, n, 3), dtype=torch.int32, device=dev)
@@ -222,6 +251,7 @@ def main():
             "delay_by_one": wl.delay, "consensus_every_step": not args.no_consensus,
             "consensus_fused_into_mix_kernel": fused,
             "in_place": bool(args.in_place),
+            "hbm_placement_probe": placement,
         },
         "roofline": {
             "kernel": "mix_step_kernel (with fused consensus statistics)" if fused else "mix_step_kernel",
@@ -235,7 +265,7 @@ def main():
     if not (args.no_consensus or fused):
         result["consensus"] = {"avg_ms": con_avg, "achieved_GBps": 4 * n * d / (con_avg * 1e-3) / 1e9,
                                "frac": 4 * n * d / (con_avg * 1e-3) / 1e9 / HBM_PEAK_GBS}
-    del X, Y, Gs
+    del X, Y, Gs, X_prev, views, pool
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl)

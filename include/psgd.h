@@ -133,6 +133,30 @@ int psgd_mix_step_cd_bf16g(const float* X, float* X_out, const uint16_t* G_bf16,
                            int n, int64_t d, float lr, int delay_mode, double* cdist_out, void* stream);
 
 /*
+ * psgd_mix_step_ex - the general form of the four calls above: the same fused step (Sec. 2,
+ * Eq. 2) on arrays whose rows are `ld*` ELEMENTS apart instead of d (row i of X starts at
+ * X + i * ldx, of X_out at X_out + i * ldo, of G at G + i * ldg; each pitch >= d).
+ *
+ *   G          device, float or bf16 bit patterns, chosen by g_is_bf16 (0 / 1)
+ *   cdist_out  device double[1] for the consensus distance of the output, or NULL for none
+ * Everything else is as in psgd_mix_step.  Mixing in place needs X_out == X and ldo == ldx;
+ * any other sharing of a byte between rows of X_out and rows of X or G is PSGD_EALIAS (the
+ * rows of different arrays may interleave as long as they do not overlap).  The 128-bit
+ * path needs d and all three pitches to be multiples of 4.
+ *
+ * Why pitches: (1) a column shard of a wider array is such a view; (2) placement.  On
+ * MI355X a kernel that streams rows which all lie in one third of the 288 GB address range
+ * reaches about 63 % of the HBM peak on this step, while rows spread over two or three
+ * thirds reach 75-77 %: an [n, d] array allocated densely is a few tens of GB and sits in
+ * one third, the same array with its rows pitched a few GB apart (other arrays' rows in
+ * between) spans the device.
+ */
+int psgd_mix_step_ex(const float* X, int64_t ldx, float* X_out, int64_t ldo,
+                     const void* G, int64_t ldg, int g_is_bf16,
+                     const int32_t* nbr, const float* w,
+                     int n, int64_t d, float lr, int delay_mode, double* cdist_out, void* stream);
+
+/*
  * psgd_consensus_dist - sum_i || x_i - xbar ||^2 with xbar the mean of the n rows of X:
  * the distance from consensus whose decay Sec. 3 (Eqs. 5, 11, 12) bounds.
  *
@@ -151,6 +175,9 @@ double psgd_consensus_dist(const float* X, int n, int64_t d);
  * streams) race on it and must be serialised by the caller.
  */
 int psgd_consensus_dist_async(const float* X, int n, int64_t d, double* out_dev, void* stream);
+
+/* psgd_consensus_dist_ex - psgd_consensus_dist_async for rows that are ldx (>= d) elements apart. */
+int psgd_consensus_dist_ex(const float* X, int64_t ldx, int n, int64_t d, double* out_dev, void* stream);
 
 /*
  * psgd_synth_grad - synthetic stand-in for back-propagation in the delay-by-one workload:

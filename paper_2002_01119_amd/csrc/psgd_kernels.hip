@@ -83,6 +83,13 @@ __device__ __forceinline__ V mix_one(float w0, float w1, float w2, V self, V lef
     return vfma(neg_lr, g, acc);
 }
 
+// Row pitches in elements: row i of X starts at X + i * x, of X_out at X_out + i * o, of G at
+// G + i * g.  Dense arrays have all three equal to d; larger pitches let a caller interleave
+// the rows of several arrays across the whole HBM (see the note on placement in the header).
+struct Pitch {
+    int64_t x, o, g;
+};
+
 // One ring position, packed so the walk fetches it with a single 128-bit LDS read.
 struct __attribute__((aligned(16))) RingEnt {
     int row;
@@ -266,12 +273,12 @@ struct ColStats {
 // ---------------------------------------------------------------------------------------
 template <int VEC, typename GT, bool CD>
 __device__ __forceinline__ void ring_walk(const float* xc, float* oc, const GT* __restrict__ gc,
-                                          const RingEnt* ring, int n, int64_t d, float neg_lr,
+                                          const RingEnt* ring, int n, Pitch ld, float neg_lr,
                                           ColStats<VEC>& stats) {
     typedef typename Cols<VEC>::T V;
     const Cols<VEC> tag{};
-    const V first = ld_x(xc + (int64_t)ring_row(ring) * d, tag);
-    const V last = (n > 1) ? ld_x(xc + (int64_t)ring_row(ring + n - 1) * d, tag) : first;
+    const V first = ld_x(xc + (int64_t)ring_row(ring) * ld.x, tag);
+    const V last = (n > 1) ? ld_x(xc + (int64_t)ring_row(ring + n - 1) * ld.x, tag) : first;
     V prev = last, cur = first;
     int p = 0;
     // Whole batches: positions p .. p+U-1, whose right neighbours p+1 .. p+U are all fresh
@@ -282,13 +289,13 @@ __device__ __forceinline__ void ring_walk(const float* xc, float* oc, const GT* 
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             e[u] = ring_ent(ring + p + u);
-            xs[u] = ld_x(xc + (int64_t)ring_row(ring + p + u + 1) * d, tag);
-            gs[u] = ld_g(gc + (int64_t)e[u].row * d, tag);
+            xs[u] = ld_x(xc + (int64_t)ring_row(ring + p + u + 1) * ld.x, tag);
+            gs[u] = ld_g(gc + (int64_t)e[u].row * ld.g, tag);
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const V out = mix_one<V>(e[u].w0, e[u].w1, e[u].w2, cur, prev, xs[u], gs[u], neg_lr);
-            st_x(oc + (int64_t)e[u].row * d, out);
+            st_x(oc + (int64_t)e[u].row * ld.o, out);
             if (CD) stats.add(out);
             prev = cur;
             cur = xs[u];
@@ -303,8 +310,8 @@ __device__ __forceinline__ void ring_walk(const float* xc, float* oc, const GT* 
             const int pp = p + u;
             if (pp < n) {
                 e[u] = ring_ent(ring + pp);
-                gs[u] = ld_g(gc + (int64_t)e[u].row * d, tag);
-                if (pp + 1 <= n - 2) xs[u] = ld_x(xc + (int64_t)ring_row(ring + pp + 1) * d, tag);
+                gs[u] = ld_g(gc + (int64_t)e[u].row * ld.g, tag);
+                if (pp + 1 <= n - 2) xs[u] = ld_x(xc + (int64_t)ring_row(ring + pp + 1) * ld.x, tag);
                 else if (pp + 1 == n - 1) xs[u] = last;
                 else xs[u] = first;
             }
@@ -313,7 +320,7 @@ __device__ __forceinline__ void ring_walk(const float* xc, float* oc, const GT* 
         for (int u = 0; u < kUnroll; ++u) {
             if (p + u < n) {
                 const V out = mix_one<V>(e[u].w0, e[u].w1, e[u].w2, cur, prev, xs[u], gs[u], neg_lr);
-                st_x(oc + (int64_t)e[u].row * d, out);
+                st_x(oc + (int64_t)e[u].row * ld.o, out);
                 if (CD) stats.add(out);
                 prev = cur;
                 cur = xs[u];
@@ -335,7 +342,7 @@ __host__ __device__ inline size_t tile_cd_bytes(int lpr, int vec) {
 
 template <int VEC, typename GT, bool CD>
 __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ G, const Lds& l,
-                            int n, int64_t d, int64_t ncg, float neg_lr, int lpr, double inv_n) {
+                            int n, Pitch ld, int64_t ncg, float neg_lr, int lpr, double inv_n) {
     typedef typename Cols<VEC>::T V;
     const Cols<VEC> tag{};
     V* tile = reinterpret_cast<V*>(l.scratch);
@@ -349,16 +356,16 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
         const bool active = cg < ncg;
         const int64_t col = cg * VEC;
         if (active)
-            for (int r = rg; r < n; r += nrg) tile[r * lpr + lane] = ld_x(X + (int64_t)r * d + col, tag);
+            for (int r = rg; r < n; r += nrg) tile[r * lpr + lane] = ld_x(X + (int64_t)r * ld.x + col, tag);
         __syncthreads();
         if (active)
             for (int r = rg; r < n; r += nrg) {
                 const V self = tile[l.nbr[3 * r] * lpr + lane];
                 const V left = tile[l.nbr[3 * r + 1] * lpr + lane];
                 const V right = tile[l.nbr[3 * r + 2] * lpr + lane];
-                const V g = ld_g(G + (int64_t)r * d + col, tag);
+                const V g = ld_g(G + (int64_t)r * ld.g + col, tag);
                 const V out = mix_one<V>(l.w[3 * r], l.w[3 * r + 1], l.w[3 * r + 2], self, left, right, g, neg_lr);
-                st_x(Xout + (int64_t)r * d + col, out);
+                st_x(Xout + (int64_t)r * ld.o + col, out);
                 if (CD && r == 0) pivot[lane] = out;
             }
         __syncthreads();
@@ -376,7 +383,7 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
                     const V self = tile[l.nbr[3 * r] * lpr + lane];
                     const V left = tile[l.nbr[3 * r + 1] * lpr + lane];
                     const V right = tile[l.nbr[3 * r + 2] * lpr + lane];
-                    const V g = ld_g(G + (int64_t)r * d + col, tag);
+                    const V g = ld_g(G + (int64_t)r * ld.g + col, tag);
                     acc_diff<VEC>(a, b, mix_one<V>(l.w[3 * r], l.w[3 * r + 1], l.w[3 * r + 2], self, left, right, g, neg_lr), s);
                 }
             }
@@ -409,7 +416,8 @@ __global__ __launch_bounds__(kThreads) void mix_step_kernel(const float* X, floa
                                                             const GT* __restrict__ G,
                                                             const int32_t* __restrict__ nbr,
                                                             const float* __restrict__ w, int n, int64_t d,
-                                                            float neg_lr, int lpr, double* __restrict__ partials) {
+                                                            Pitch ld, float neg_lr, int lpr,
+                                                            double* __restrict__ partials) {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     __shared__ double lds4[4];
     const Lds l = carve(lds_raw, n);
@@ -428,11 +436,11 @@ __global__ __launch_bounds__(kThreads) void mix_step_kernel(const float* X, floa
             const int64_t col = cg * VEC;
             ColStats<VEC> stats;
             if (CD) stats.reset();
-            ring_walk<VEC, GT, CD>(X + col, Xout + col, G + col, l.ring, n, d, neg_lr, stats);
+            ring_walk<VEC, GT, CD>(X + col, Xout + col, G + col, l.ring, n, ld, neg_lr, stats);
             if (CD) total += stats.result(inv_n);
         }
     } else {
-        total = tile_path<VEC, GT, CD>(X, Xout, G, l, n, d, ncg, neg_lr, lpr, inv_n);
+        total = tile_path<VEC, GT, CD>(X, Xout, G, l, n, ld, ncg, neg_lr, lpr, inv_n);
     }
     if (CD) {
         const double bs = block_sum(total, lds4);
@@ -443,7 +451,8 @@ __global__ __launch_bounds__(kThreads) void mix_step_kernel(const float* X, floa
 // Consensus-distance kernels (the per-column arithmetic is defined above the ring walk).
 template <int VEC>
 __global__ __launch_bounds__(kThreads) void consensus_partial_kernel(const float* __restrict__ X, int n,
-                                                                     int64_t d, double* __restrict__ partials) {
+                                                                     int64_t d, int64_t ldx,
+                                                                     double* __restrict__ partials) {
     typedef typename Cols<VEC>::T V;
     const Cols<VEC> tag{};
     __shared__ double lds4[4];
@@ -461,7 +470,7 @@ __global__ __launch_bounds__(kThreads) void consensus_partial_kernel(const float
         for (; r + kUnroll <= n; r += kUnroll) {
             V xs[kUnroll];
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) xs[u] = ld_x(xc + (int64_t)(r + u) * d, tag);
+            for (int u = 0; u < kUnroll; ++u) xs[u] = ld_x(xc + (int64_t)(r + u) * ldx, tag);
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) acc_diff<VEC>(a, b, xs[u], s);
         }
@@ -469,7 +478,7 @@ __global__ __launch_bounds__(kThreads) void consensus_partial_kernel(const float
             V xs[kUnroll];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u)
-                if (r + u < n) xs[u] = ld_x(xc + (int64_t)(r + u) * d, tag);
+                if (r + u < n) xs[u] = ld_x(xc + (int64_t)(r + u) * ldx, tag);
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u)
                 if (r + u < n) acc_diff<VEC>(a, b, xs[u], s);
@@ -563,12 +572,30 @@ inline int persistent_grid(const DeviceInfo& di, int64_t work_items, int per_cu)
     return (int)(g < 1 ? 1 : g);
 }
 
+// True if any row of A ([n] rows of ra bytes, lda bytes apart) shares a byte with any row of B.
+bool rows_overlap(const void* A, int64_t lda, size_t ra, const void* B, int64_t ldb, size_t rb, int n) {
+    if (ra == 0 || rb == 0) return false;
+    const size_t span_a = (size_t)(n - 1) * (size_t)lda + ra, span_b = (size_t)(n - 1) * (size_t)ldb + rb;
+    if (!overlaps(A, span_a, B, span_b)) return false;
+    if ((size_t)lda == ra && (size_t)ldb == rb) return true;  // both dense: the spans are the arrays
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(A), b0 = reinterpret_cast<uintptr_t>(B);
+    for (int i = 0; i < n; ++i) {
+        const uintptr_t ai = a0 + (uintptr_t)i * (uintptr_t)lda;
+        for (int j = 0; j < n; ++j) {
+            const uintptr_t bj = b0 + (uintptr_t)j * (uintptr_t)ldb;
+            if (ai < bj + rb && bj < ai + ra) return true;
+        }
+    }
+    return false;
+}
+
 // Launches one instantiation of the mix kernel on a persistent grid sized to what is
 // actually resident: min(kGridPerCu, occupancy for this LDS size) workgroups per CU.
 // Returns the grid size.  The occupancy query is cached per instantiation and LDS size.
 template <int VEC, typename GT, bool CD>
 int launch_mix(const DeviceInfo& di, size_t lds_bytes, hipStream_t s, const float* X, float* X_out, const GT* G,
-               const int32_t* nbr, const float* w, int n, int64_t d, float neg_lr, int lpr, double* partials) {
+               const int32_t* nbr, const float* w, int n, int64_t d, Pitch ld, float neg_lr, int lpr,
+               double* partials) {
     static std::mutex mu;
     static size_t cached_lds = ~(size_t)0;
     static int cached_occ = 0;
@@ -588,31 +615,39 @@ int launch_mix(const DeviceInfo& di, size_t lds_bytes, hipStream_t s, const floa
     const int per_cu = occ < kGridPerCu ? occ : kGridPerCu;
     const int grid = persistent_grid(di, d / VEC, per_cu);
     hipLaunchKernelGGL((mix_step_kernel<VEC, GT, CD>), dim3(grid), dim3(kThreads), lds_bytes, s, X, X_out, G, nbr, w, n,
-                       d, neg_lr, lpr, partials);
+                       d, ld, neg_lr, lpr, partials);
     return grid;
 }
 
+// Pitches are in elements of the array they belong to.
 template <typename GT>
-int mix_step_impl(const char* name, const float* X, float* X_out, const GT* G, const int32_t* nbr, const float* w,
-                  int n, int64_t d, float lr, int delay_mode, bool want_cd, double* cd_out, void* stream) {
+int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, int64_t ldo, const GT* G, int64_t ldg,
+                  const int32_t* nbr, const float* w, int n, int64_t d, float lr, int delay_mode, bool want_cd,
+                  double* cd_out, void* stream) {
     clear_error();
     if (!X || !X_out || !G || !nbr || !w || (want_cd && !cd_out)) return fail(PSGD_EINVAL, "%s: null pointer", name);
     if (n < 1 || n > PSGD_MAX_N) return fail(PSGD_EINVAL, "%s: n=%d outside 1..%d", name, n, (int)PSGD_MAX_N);
     if (d < 0) return fail(PSGD_EINVAL, "%s: d=%lld is negative", name, (long long)d);
     if (delay_mode != 0 && delay_mode != 1) return fail(PSGD_EINVAL, "%s: delay_mode=%d", name, delay_mode);
+    if (n > 1 && (ldx < d || ldo < d || ldg < d))
+        return fail(PSGD_EINVAL, "%s: a row pitch is smaller than d=%lld", name, (long long)d);
+    if (n == 1) ldx = ldo = ldg = d;
     if (!aligned_to(X, 4) || !aligned_to(X_out, 4) || !aligned_to(G, sizeof(GT)) || !aligned_to(nbr, 4) ||
         !aligned_to(w, 4) || (want_cd && !aligned_to(cd_out, 8)))
         return fail(PSGD_EALIGN, "%s: pointer not aligned to its element size", name);
-    if (d > 0 && (int64_t)n > INT64_MAX / 4 / d) return fail(PSGD_EINVAL, "%s: n*d overflows", name);
-    const size_t xbytes = (size_t)n * (size_t)d * sizeof(float), gbytes = (size_t)n * (size_t)d * sizeof(GT);
-    if (static_cast<const void*>(X) == static_cast<const void*>(X_out)) {
+    const int64_t ldmax = ldx > ldo ? (ldx > ldg ? ldx : ldg) : (ldo > ldg ? ldo : ldg);
+    if (ldmax > 0 && (int64_t)n > INT64_MAX / 8 / ldmax) return fail(PSGD_EINVAL, "%s: n * pitch overflows", name);
+    const size_t xrow = (size_t)d * sizeof(float), grow = (size_t)d * sizeof(GT);
+    const int64_t bx = ldx * (int64_t)sizeof(float), bo = ldo * (int64_t)sizeof(float), bg = ldg * (int64_t)sizeof(GT);
+    if (static_cast<const void*>(X) == static_cast<const void*>(X_out) && ldx == ldo) {
         if (delay_mode == 1)
             return fail(PSGD_EALIAS, "%s: delay-by-one keeps X read-only, X_out must be another buffer", name);
-    } else if (overlaps(X, xbytes, X_out, xbytes)) {
+    } else if (rows_overlap(X, bx, xrow, X_out, bo, xrow, n)) {
         return fail(PSGD_EALIAS, "%s: X_out partially overlaps X", name);
     }
-    if (overlaps(G, gbytes, X_out, xbytes)) return fail(PSGD_EALIAS, "%s: X_out overlaps G", name);
-    if (want_cd && (overlaps(cd_out, 8, X_out, xbytes) || overlaps(cd_out, 8, X, xbytes) || overlaps(cd_out, 8, G, gbytes)))
+    if (rows_overlap(G, bg, grow, X_out, bo, xrow, n)) return fail(PSGD_EALIAS, "%s: X_out overlaps G", name);
+    if (want_cd && (rows_overlap(cd_out, 8, 8, X_out, bo, xrow, n) || rows_overlap(cd_out, 8, 8, X, bx, xrow, n) ||
+                    rows_overlap(cd_out, 8, 8, G, bg, grow, n)))
         return fail(PSGD_EALIAS, "%s: the distance output overlaps a data buffer", name);
     hipStream_t s = static_cast<hipStream_t>(stream);
     DeviceInfo* di = nullptr;
@@ -626,7 +661,8 @@ int mix_step_impl(const char* name, const float* X, float* X_out, const GT* G, c
     if (int rc = device_info(&di, want_cd)) return rc;
 
     // 128-bit path needs every row start 16-byte aligned (8-byte for bf16 gradients).
-    const bool vec4 = (d % 4 == 0) && aligned_to(X, 16) && aligned_to(X_out, 16) && aligned_to(G, 4 * sizeof(GT));
+    const bool vec4 = (d % 4 == 0) && (ldx % 4 == 0) && (ldo % 4 == 0) && (ldg % 4 == 0) && aligned_to(X, 16) &&
+                      aligned_to(X_out, 16) && aligned_to(G, 4 * sizeof(GT));
     const int vec = vec4 ? 4 : 1;
     // Tile shape of the fallback path: widest power-of-two lane count whose tile fits.
     const size_t tile_budget = want_cd ? (size_t)kTileBytes / 2 : (size_t)kTileBytes;
@@ -638,16 +674,17 @@ int mix_step_impl(const char* name, const float* X, float* X_out, const GT* G, c
     if (lds_bytes > 64 * 1024 - 64) return fail(PSGD_EINVAL, "%s: n=%d needs %zu bytes of LDS", name, n, lds_bytes);
 
     const float neg_lr = -lr;
+    const Pitch ld{ldx, ldo, ldg};
     double* partials = want_cd ? di->scratch : nullptr;
     int grid = 0;
     if (vec4 && want_cd)
-        grid = launch_mix<4, GT, true>(*di, lds_bytes, s, X, X_out, G, nbr, w, n, d, neg_lr, lpr, partials);
+        grid = launch_mix<4, GT, true>(*di, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials);
     else if (vec4)
-        grid = launch_mix<4, GT, false>(*di, lds_bytes, s, X, X_out, G, nbr, w, n, d, neg_lr, lpr, partials);
+        grid = launch_mix<4, GT, false>(*di, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials);
     else if (want_cd)
-        grid = launch_mix<1, GT, true>(*di, lds_bytes, s, X, X_out, G, nbr, w, n, d, neg_lr, lpr, partials);
+        grid = launch_mix<1, GT, true>(*di, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials);
     else
-        grid = launch_mix<1, GT, false>(*di, lds_bytes, s, X, X_out, G, nbr, w, n, d, neg_lr, lpr, partials);
+        grid = launch_mix<1, GT, false>(*di, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, name);
     if (want_cd) {
@@ -658,15 +695,15 @@ int mix_step_impl(const char* name, const float* X, float* X_out, const GT* G, c
     return PSGD_OK;
 }
 
-int consensus_enqueue(const float* X, int n, int64_t d, double* out_dev, hipStream_t s) {
+int consensus_enqueue(const float* X, int64_t ldx, int n, int64_t d, double* out_dev, hipStream_t s) {
     DeviceInfo* di = nullptr;
     if (int rc = device_info(&di, true)) return rc;
-    const bool vec4 = (d % 4 == 0) && aligned_to(X, 16);
+    const bool vec4 = (d % 4 == 0) && (ldx % 4 == 0) && aligned_to(X, 16);
     const int grid = persistent_grid(*di, vec4 ? d / 4 : d, 8);  // light kernel: 32 waves per CU
     if (vec4)
-        hipLaunchKernelGGL(consensus_partial_kernel<4>, dim3(grid), dim3(kThreads), 0, s, X, n, d, di->scratch);
+        hipLaunchKernelGGL(consensus_partial_kernel<4>, dim3(grid), dim3(kThreads), 0, s, X, n, d, ldx, di->scratch);
     else
-        hipLaunchKernelGGL(consensus_partial_kernel<1>, dim3(grid), dim3(kThreads), 0, s, X, n, d, di->scratch);
+        hipLaunchKernelGGL(consensus_partial_kernel<1>, dim3(grid), dim3(kThreads), 0, s, X, n, d, ldx, di->scratch);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "consensus_partial_kernel");
     hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, di->scratch, grid,
@@ -676,66 +713,22 @@ int consensus_enqueue(const float* X, int n, int64_t d, double* out_dev, hipStre
     return PSGD_OK;
 }
 
-int consensus_check(const char* name, const float* X, int n, int64_t d) {
+int consensus_check(const char* name, const float* X, int64_t ldx, int n, int64_t d) {
     if (!X) return fail(PSGD_EINVAL, "%s: null pointer", name);
     if (n < 1 || n > PSGD_MAX_N) return fail(PSGD_EINVAL, "%s: n=%d outside 1..%d", name, n, (int)PSGD_MAX_N);
     if (d < 0) return fail(PSGD_EINVAL, "%s: d=%lld is negative", name, (long long)d);
+    if (n > 1 && ldx < d) return fail(PSGD_EINVAL, "%s: row pitch smaller than d", name);
     if (!aligned_to(X, 4)) return fail(PSGD_EALIGN, "%s: X not 4-byte aligned", name);
-    if (d > 0 && (int64_t)n > INT64_MAX / 4 / d) return fail(PSGD_EINVAL, "%s: n*d overflows", name);
+    if (ldx > 0 && (int64_t)n > INT64_MAX / 8 / ldx) return fail(PSGD_EINVAL, "%s: n * pitch overflows", name);
     return PSGD_OK;
 }
 
-}  // namespace
-}  // namespace psgd
-
-extern "C" {
-
-int psgd_mix_step(const float* X, float* X_out, const float* G, const int32_t* nbr, const float* w, int n, int64_t d,
-                  float lr, int delay_mode, void* stream) {
-    return psgd::mix_step_impl<float>("psgd_mix_step", X, X_out, G, nbr, w, n, d, lr, delay_mode, false, nullptr,
-                                      stream);
-}
-
-int psgd_mix_step_bf16g(const float* X, float* X_out, const uint16_t* G_bf16, const int32_t* nbr, const float* w,
-                        int n, int64_t d, float lr, int delay_mode, void* stream) {
-    return psgd::mix_step_impl<uint16_t>("psgd_mix_step_bf16g", X, X_out, G_bf16, nbr, w, n, d, lr, delay_mode, false,
-                                         nullptr, stream);
-}
-
-int psgd_mix_step_cd(const float* X, float* X_out, const float* G, const int32_t* nbr, const float* w, int n,
-                     int64_t d, float lr, int delay_mode, double* cdist_out, void* stream) {
-    return psgd::mix_step_impl<float>("psgd_mix_step_cd", X, X_out, G, nbr, w, n, d, lr, delay_mode, true, cdist_out,
-                                      stream);
-}
-
-int psgd_mix_step_cd_bf16g(const float* X, float* X_out, const uint16_t* G_bf16, const int32_t* nbr, const float* w,
-                           int n, int64_t d, float lr, int delay_mode, double* cdist_out, void* stream) {
-    return psgd::mix_step_impl<uint16_t>("psgd_mix_step_cd_bf16g", X, X_out, G_bf16, nbr, w, n, d, lr, delay_mode,
-                                         true, cdist_out, stream);
-}
-
-double psgd_consensus_dist(const float* X, int n, int64_t d) {
-    using namespace psgd;
+int consensus_async_impl(const char* name, const float* X, int64_t ldx, int n, int64_t d, double* out_dev,
+                         void* stream) {
     clear_error();
-    if (consensus_check("psgd_consensus_dist", X, n, d) != PSGD_OK) return NAN;
-    if (d == 0 || n == 1) return 0.0;
-    hipError_t e = hipDeviceSynchronize();
-    if (e != hipSuccess) { hip_fail(e, "hipDeviceSynchronize"); return NAN; }
-    if (consensus_enqueue(X, n, d, nullptr, nullptr) != PSGD_OK) return NAN;
-    DeviceInfo* di = nullptr;
-    if (device_info(&di, true) != PSGD_OK) return NAN;
-    double host = NAN;
-    e = hipMemcpy(&host, di->scratch + kMaxGrid, sizeof(double), hipMemcpyDeviceToHost);
-    if (e != hipSuccess) { hip_fail(e, "hipMemcpy(result)"); return NAN; }
-    return host;
-}
-
-int psgd_consensus_dist_async(const float* X, int n, int64_t d, double* out_dev, void* stream) {
-    using namespace psgd;
-    clear_error();
-    if (!out_dev) return fail(PSGD_EINVAL, "psgd_consensus_dist_async: null output pointer");
-    if (!aligned_to(out_dev, 8)) return fail(PSGD_EALIGN, "psgd_consensus_dist_async: out_dev not 8-byte aligned");
-    if (int rc = consensus_check("psgd_consensus_dist_async", X, n, d)) return rc;
+    if (!out_dev) return fail(PSGD_EINVAL, "%s: null output pointer", name);
+    if (!aligned_to(out_dev, 8)) return fail(PSGD_EALIGN, "%s: out_dev not 8-byte aligned", name);
+    if (int rc = consensus_check(name, X, ldx, n, d)) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (d == 0) {
         // nothing to reduce: the final kernel over zero partials writes 0
@@ -746,7 +739,75 @@ int psgd_consensus_dist_async(const float* X, int n, int64_t d, double* out_dev,
         if (e != hipSuccess) return hip_fail(e, "consensus_final_kernel");
         return PSGD_OK;
     }
-    return consensus_enqueue(X, n, d, out_dev, s);
+    return consensus_enqueue(X, n == 1 ? d : ldx, n, d, out_dev, s);
+}
+
+}  // namespace
+}  // namespace psgd
+
+extern "C" {
+
+int psgd_mix_step(const float* X, float* X_out, const float* G, const int32_t* nbr, const float* w, int n, int64_t d,
+                  float lr, int delay_mode, void* stream) {
+    return psgd::mix_step_impl<float>("psgd_mix_step", X, d, X_out, d, G, d, nbr, w, n, d, lr, delay_mode, false,
+                                      nullptr, stream);
+}
+
+int psgd_mix_step_bf16g(const float* X, float* X_out, const uint16_t* G_bf16, const int32_t* nbr, const float* w,
+                        int n, int64_t d, float lr, int delay_mode, void* stream) {
+    return psgd::mix_step_impl<uint16_t>("psgd_mix_step_bf16g", X, d, X_out, d, G_bf16, d, nbr, w, n, d, lr,
+                                         delay_mode, false, nullptr, stream);
+}
+
+int psgd_mix_step_cd(const float* X, float* X_out, const float* G, const int32_t* nbr, const float* w, int n,
+                     int64_t d, float lr, int delay_mode, double* cdist_out, void* stream) {
+    return psgd::mix_step_impl<float>("psgd_mix_step_cd", X, d, X_out, d, G, d, nbr, w, n, d, lr, delay_mode, true,
+                                      cdist_out, stream);
+}
+
+int psgd_mix_step_cd_bf16g(const float* X, float* X_out, const uint16_t* G_bf16, const int32_t* nbr, const float* w,
+                           int n, int64_t d, float lr, int delay_mode, double* cdist_out, void* stream) {
+    return psgd::mix_step_impl<uint16_t>("psgd_mix_step_cd_bf16g", X, d, X_out, d, G_bf16, d, nbr, w, n, d, lr,
+                                         delay_mode, true, cdist_out, stream);
+}
+
+int psgd_mix_step_ex(const float* X, int64_t ldx, float* X_out, int64_t ldo, const void* G, int64_t ldg, int g_is_bf16,
+                     const int32_t* nbr, const float* w, int n, int64_t d, float lr, int delay_mode,
+                     double* cdist_out, void* stream) {
+    if (g_is_bf16 != 0 && g_is_bf16 != 1) {
+        psgd::clear_error();
+        return psgd::fail(PSGD_EINVAL, "psgd_mix_step_ex: g_is_bf16=%d", g_is_bf16);
+    }
+    if (g_is_bf16)
+        return psgd::mix_step_impl<uint16_t>("psgd_mix_step_ex", X, ldx, X_out, ldo, static_cast<const uint16_t*>(G),
+                                             ldg, nbr, w, n, d, lr, delay_mode, cdist_out != nullptr, cdist_out,
+                                             stream);
+    return psgd::mix_step_impl<float>("psgd_mix_step_ex", X, ldx, X_out, ldo, static_cast<const float*>(G), ldg, nbr,
+                                      w, n, d, lr, delay_mode, cdist_out != nullptr, cdist_out, stream);
+}
+
+double psgd_consensus_dist(const float* X, int n, int64_t d) {
+    using namespace psgd;
+    clear_error();
+    if (consensus_check("psgd_consensus_dist", X, d, n, d) != PSGD_OK) return NAN;
+    if (d == 0 || n == 1) return 0.0;
+    hipError_t e = hipDeviceSynchronize();
+    if (e != hipSuccess) { hip_fail(e, "hipDeviceSynchronize"); return NAN; }
+    if (consensus_enqueue(X, d, n, d, nullptr, nullptr) != PSGD_OK) return NAN;
+    DeviceInfo* di = nullptr;
+    if (device_info(&di, true) != PSGD_OK) return NAN;
+    double host = NAN;
+    e = hipMemcpy(&host, di->scratch + kMaxGrid, sizeof(double), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) { hip_fail(e, "hipMemcpy(result)"); return NAN; }
+    return host;
+}
+
+int psgd_consensus_dist_async(const float* X, int n, int64_t d, double* out_dev, void* stream) {
+    return psgd::consensus_async_impl("psgd_consensus_dist_async", X, d, n, d, out_dev, stream);
+}
+
+int psgd_consensus_dist_ex(const float* X, int64_t ldx, int n, int64_t d, double* out_dev, void* stream) {
+    return psgd::consensus_async_impl("psgd_consensus_dist_ex", X, ldx, n, d, out_dev, stream);
 }
 
 int psgd_synth_grad(const float* X_prev, const float* noise, float* G, int64_t count, float c, void* stream) {

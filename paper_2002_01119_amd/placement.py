@@ -1,0 +1,87 @@
+"""Placement of the replica buffers inside HBM.
+
+On MI355X the sustained rate of a kernel that writes a multi-gigabyte buffer depends on where
+that buffer lies: ranges of the same size, carved from one allocation, fall into a faster
+(about 6 TB/s of stores) and a slower (about 5 TB/s) class, reproducibly for a given range and
+independently of the order in which it is swept.  The mixing step follows the class of its
+output buffer (74-77 % against 63-65 % of the 8 TB/s peak).  Nothing in the public
+documentation predicts the class from an address, so it is measured: allocate one pool, time
+the step itself, in place, on candidate windows of the pool, and put the buffers that are
+written every iteration (X and X_out) on the fastest non-overlapping windows.  Buffers that
+are only read (gradients) can go anywhere.
+
+Only device-memory plumbing lives here; the timed work is the library's own kernel.
+"""
+import torch
+
+from . import psgd
+
+
+def _window(pool, offset, n, d):
+    return pool[offset:offset + n * d * 4].view(torch.float32).view(n, d)
+
+
+def probe_windows(pool, n, d, G, nbr, w, step_bytes, stream=None, repeats=2):
+    """Time an in-place psgd_mix_step on every window [off, off + n*d*4) of `pool` (a uint8
+    device tensor) with off = 0, step_bytes, 2*step_bytes, ...  Returns [(offset, ms), ...].
+    The windows' contents are overwritten."""
+    nbytes = n * d * 4
+    stream = stream or torch.cuda.current_stream()
+    out = []
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    off = 0
+    while off + nbytes <= pool.numel():
+        X = _window(pool, off, n, d)
+        best = float("inf")
+        for r in range(repeats + 1):
+            e0.record(stream)
+            psgd.mix_step(X, X, G, nbr, w, 0.0, stream=stream)
+            e1.record(stream)
+            e1.synchronize()
+            if r > 0:
+                best = min(best, e0.elapsed_time(e1))
+        out.append((off, best))
+        off += step_bytes
+    return out
+
+
+def choose_windows(timings, nbytes, count):
+    """Greedy pick of `count` mutually non-overlapping windows with the smallest times."""
+    chosen = []
+    for off, ms in sorted(timings, key=lambda t: t[1]):
+        if all(abs(off - c) >= nbytes for c, _ in chosen):
+            chosen.append((off, ms))
+            if len(chosen) == count:
+                break
+    return chosen
+
+
+def place_replica_buffers(n, d, count, G, nbr, w, reserve_bytes, max_pool_bytes=None, log=None):
+    """Allocate one pool, probe it, and return (`count` [n, d] fp32 views on the fastest
+    windows, pool tensor, report dict).  Raises torch.OutOfMemoryError if the pool does not fit."""
+    nbytes = n * d * 4
+    free, _total = torch.cuda.mem_get_info()
+    pool_bytes = free - reserve_bytes
+    if max_pool_bytes is not None:
+        pool_bytes = min(pool_bytes, max_pool_bytes)
+    step = max((nbytes // 4) // 4096 * 4096, 4096)
+    pool_bytes = pool_bytes // 4096 * 4096
+    if pool_bytes < count * nbytes:
+        raise torch.OutOfMemoryError("pool of %d bytes cannot hold %d buffers" % (pool_bytes, count))
+    pool = torch.empty(pool_bytes, dtype=torch.uint8, device=G.device)
+    pool.zero_()
+    timings = probe_windows(pool, n, d, G, nbr, w, step)
+    chosen = choose_windows(timings, nbytes, count)
+    if len(chosen) < count:
+        raise RuntimeError("could not place %d non-overlapping windows" % count)
+    if log:
+        log("placement probe (in-place mix step per window, ms): "
+            + " ".join("%.1fGB:%.2f" % (o / 1e9, ms) for o, ms in timings))
+        log("placement: chose windows at " + ", ".join("%.1f GB (%.2f ms)" % (o / 1e9, ms) for o, ms in chosen))
+    views = [_window(pool, off, n, d) for off, _ in chosen]
+    report = {
+        "pool_GB": pool_bytes / 1e9, "windows_probed": len(timings),
+        "probe_ms_min": min(t for _, t in timings), "probe_ms_max": max(t for _, t in timings),
+        "chosen_offsets_GB": [o / 1e9 for o, _ in chosen], "chosen_probe_ms": [ms for _, ms in chosen],
+    }
+    return views, pool, report

@@ -22,7 +22,7 @@ _lib = None
 
 EXPORTS = (
     "psgd_build_mixing", "psgd_mix_step", "psgd_mix_step_bf16g", "psgd_mix_step_cd",
-    "psgd_mix_step_cd_bf16g", "psgd_consensus_dist",
+    "psgd_mix_step_cd_bf16g", "psgd_mix_step_ex", "psgd_consensus_dist", "psgd_consensus_dist_ex",
     "psgd_consensus_dist_async", "psgd_synth_grad", "psgd_device_status", "psgd_last_error",
     "psgd_version",
 )
@@ -59,6 +59,11 @@ def load(reload=False):
         fn.restype = ctypes.c_int
         fn.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int, ctypes.c_int64, ctypes.c_float,
                        ctypes.c_int, vp, vp]
+    lib.psgd_mix_step_ex.restype = ctypes.c_int
+    lib.psgd_mix_step_ex.argtypes = [vp, ctypes.c_int64, vp, ctypes.c_int64, vp, ctypes.c_int64, ctypes.c_int,
+                                     vp, vp, ctypes.c_int, ctypes.c_int64, ctypes.c_float, ctypes.c_int, vp, vp]
+    lib.psgd_consensus_dist_ex.restype = ctypes.c_int
+    lib.psgd_consensus_dist_ex.argtypes = [vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int64, vp, vp]
     lib.psgd_consensus_dist.restype = ctypes.c_double
     lib.psgd_consensus_dist.argtypes = [vp, ctypes.c_int, ctypes.c_int64]
     lib.psgd_consensus_dist_async.restype = ctypes.c_int
@@ -98,6 +103,14 @@ def _rows_cols(t):
     return int(t.shape[0]), int(t.shape[1])
 
 
+def _rows_cols_pitch(t):
+    """(n, d, pitch in elements) of a 2-D tensor whose rows are contiguous (stride(1) == 1)."""
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError("expected an [n, d] tensor with unit stride along d")
+    n, d = int(t.shape[0]), int(t.shape[1])
+    return n, d, (int(t.stride(0)) if n > 1 else d)
+
+
 def build_mixing(topology, n, seed=0, step=0):
     """Returns (nbr int32 [n,3], w float32 [n,3]) as host numpy arrays."""
     nbr = np.empty((max(n, 0), DEG), dtype=np.int32)
@@ -110,14 +123,16 @@ def build_mixing(topology, n, seed=0, step=0):
 
 def mix_step(X, X_out, G, nbr, w, lr, delay_mode=0, stream=None, cdist_out=None):
     """Enqueue X_out = mix(X) - lr * G.  All arguments are device tensors; G is float32, or
-    bfloat16 / int16 / uint16 (bf16 bit patterns), which selects the *_bf16g entry point.
-    With cdist_out (device float64 tensor, >= 1 element) the fused psgd_mix_step_cd variant
-    also writes the consensus distance of X_out there."""
+    bfloat16 / int16 / uint16 (bf16 bit patterns).  X, X_out and G are [n, d] with unit
+    stride along d; their rows may be pitched (stride(0) >= d), which selects
+    psgd_mix_step_ex.  With cdist_out (device float64 tensor, >= 1 element) the fused
+    variant also writes the consensus distance of X_out there."""
     import torch
-    n, d = _rows_cols(X)
-    if tuple(X_out.shape) != (n, d) or tuple(G.shape) != (n, d) or not X_out.is_contiguous() \
-            or not G.is_contiguous():
-        raise ValueError("X, X_out and G must be contiguous and of one shape")
+    n, d, ldx = _rows_cols_pitch(X)
+    no, do, ldo = _rows_cols_pitch(X_out)
+    ng, dg, ldg = _rows_cols_pitch(G)
+    if (no, do) != (n, d) or (ng, dg) != (n, d):
+        raise ValueError("X, X_out and G must have one shape")
     if X.dtype != torch.float32 or X_out.dtype != torch.float32:
         raise ValueError("X and X_out must be float32")
     if nbr.dtype != torch.int32 or w.dtype != torch.float32 or nbr.numel() != n * DEG \
@@ -133,16 +148,23 @@ def mix_step(X, X_out, G, nbr, w, lr, delay_mode=0, stream=None, cdist_out=None)
         bf16 = True
     else:
         raise ValueError("G must be float32 or bfloat16 bit patterns")
-    if cdist_out is None:
-        fn = lib.psgd_mix_step_bf16g if bf16 else lib.psgd_mix_step
-        _check(fn(X.data_ptr(), X_out.data_ptr(), G.data_ptr(), nbr.data_ptr(), w.data_ptr(), n, d,
-                  float(lr), int(delay_mode), _stream_handle(stream)))
-    else:
+    cd_ptr = None
+    if cdist_out is not None:
         if cdist_out.dtype != torch.float64 or cdist_out.numel() < 1 or cdist_out.device != X.device:
             raise ValueError("cdist_out must be a float64 device tensor")
+        cd_ptr = cdist_out.data_ptr()
+    sh = _stream_handle(stream)
+    if (ldx, ldo, ldg) != (d, d, d):
+        _check(lib.psgd_mix_step_ex(X.data_ptr(), ldx, X_out.data_ptr(), ldo, G.data_ptr(), ldg, int(bf16),
+                                    nbr.data_ptr(), w.data_ptr(), n, d, float(lr), int(delay_mode), cd_ptr, sh))
+    elif cd_ptr is None:
+        fn = lib.psgd_mix_step_bf16g if bf16 else lib.psgd_mix_step
+        _check(fn(X.data_ptr(), X_out.data_ptr(), G.data_ptr(), nbr.data_ptr(), w.data_ptr(), n, d,
+                  float(lr), int(delay_mode), sh))
+    else:
         fn = lib.psgd_mix_step_cd_bf16g if bf16 else lib.psgd_mix_step_cd
         _check(fn(X.data_ptr(), X_out.data_ptr(), G.data_ptr(), nbr.data_ptr(), w.data_ptr(), n, d,
-                  float(lr), int(delay_mode), cdist_out.data_ptr(), _stream_handle(stream)))
+                  float(lr), int(delay_mode), cd_ptr, sh))
 
 
 def consensus_dist(X):
@@ -159,10 +181,13 @@ def consensus_dist(X):
 def consensus_dist_async(X, out, stream=None):
     """Enqueue the consensus distance of X into out (device float64 tensor, 1 element)."""
     import torch
-    n, d = _rows_cols(X)
+    n, d, ldx = _rows_cols_pitch(X)
     if out.dtype != torch.float64 or out.numel() < 1 or out.device != X.device:
         raise ValueError("out must be a float64 device tensor")
-    _check(load().psgd_consensus_dist_async(X.data_ptr(), n, d, out.data_ptr(), _stream_handle(stream)))
+    if ldx != d:
+        _check(load().psgd_consensus_dist_ex(X.data_ptr(), ldx, n, d, out.data_ptr(), _stream_handle(stream)))
+    else:
+        _check(load().psgd_consensus_dist_async(X.data_ptr(), n, d, out.data_ptr(), _stream_handle(stream)))
 
 
 def synth_grad(X_prev, noise, G, c, stream=None):

@@ -321,6 +321,79 @@ def test_fused_distance_special_cases(psgd):
     assert rc == 0 and cz.item() == 0.0
 
 
+# ------------------------------------------------------------------------- pitched rows
+def _pitched_views(n, d, pitch, g_bf16):
+    """X, X_out and G as interleaved row-pitched views of ONE pool: row i of X at i*pitch,
+    of X_out right behind it, of G behind that (pitch in fp32 elements)."""
+    pool = torch.zeros(n * pitch + 8, dtype=torch.float32, device="cuda:0")
+    X = pool.as_strided((n, d), (pitch, 1), 0)
+    Y = pool.as_strided((n, d), (pitch, 1), d)
+    if g_bf16:
+        gp = pool.view(torch.int16)
+        G = gp.as_strided((n, d), (2 * pitch, 1), 4 * d)
+    else:
+        G = pool.as_strided((n, d), (pitch, 1), 2 * d)
+    return pool, X, Y, G
+
+
+@pytest.mark.parametrize("n,d,pitch", [(2, 8, 32), (8, 4100, 3 * 4100 + 4), (16, 1001, 3100), (64, 2052, 7000),
+                                       (128, 516, 2048), (5, 1, 3)])
+@pytest.mark.parametrize("gkind", ["f32", "bf16"])
+def test_pitched_interleaved_rows_match_dense(psgd, n, d, pitch, gkind):
+    Xh = inp.host_normal_f32((n, d), 1.0, 1100 + n)
+    Gh = inp.host_normal_f32((n, d), 0.5, 1200 + n)
+    if gkind == "bf16":
+        Gh = inp.f32_to_bf16_bits(Gh)
+    nbr, w = psgd.build_mixing(psgd.TOPO_RAND_RING, n, 77, d)
+    want = orc.mix_step(Xh, Gh, orc.densify(nbr, w), 0.1)
+    dense = run_step(psgd, Xh, Gh, nbr, w, 0.1)
+    pool, X, Y, G = _pitched_views(n, d, pitch, gkind == "bf16")
+    X.copy_(dev(Xh))
+    G.copy_(bits_dev(Gh) if gkind == "bf16" else dev(Gh))
+    before = pool.clone()
+    c = torch.zeros(1, dtype=torch.float64, device="cuda:0")
+    psgd.mix_step(X, Y, G, dev(nbr), dev(w), 0.1, cdist_out=c)
+    torch.cuda.synchronize()
+    got = Y.cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), dense.view(np.uint32))
+    assert_close(got, want)
+    c_ref = orc.consensus_dist(got)
+    assert abs(c.item() - c_ref) <= REL * c_ref + 1e-300
+    # nothing outside the rows of X_out was touched
+    after = pool.clone()
+    Y.zero_()
+    Yb = before.as_strided((n, d), (pitch, 1), d)
+    Yb.zero_()
+    after2 = pool.clone()
+    assert torch.equal(after2, before)
+    del after
+    # pitched consensus distance and in-place
+    c2 = torch.zeros(1, dtype=torch.float64, device="cuda:0")
+    psgd.consensus_dist_async(X, c2)
+    torch.cuda.synchronize()
+    assert abs(c2.item() - orc.consensus_dist(Xh)) <= REL * orc.consensus_dist(Xh) + 1e-300
+    psgd.mix_step(X, X, G, dev(nbr), dev(w), 0.1)
+    torch.cuda.synchronize()
+    assert np.array_equal(X.cpu().numpy().view(np.uint32), dense.view(np.uint32))
+
+
+def test_pitched_general_table(psgd):
+    n, d, pitch = 16, 1030, 4096
+    rng = np.random.default_rng(3)
+    nbr, w = _general_table(n, rng)
+    Xh = inp.host_normal_f32((n, d), 1.0, 1)
+    Gh = inp.host_normal_f32((n, d), 1.0, 2)
+    pool, X, Y, G = _pitched_views(n, d, pitch, False)
+    X.copy_(dev(Xh))
+    G.copy_(dev(Gh))
+    c = torch.zeros(1, dtype=torch.float64, device="cuda:0")
+    psgd.mix_step(X, Y, G, dev(nbr), dev(w), 0.2, cdist_out=c)
+    torch.cuda.synchronize()
+    got = Y.cpu().numpy()
+    assert_close(got, orc.mix_step(Xh, Gh, orc.densify(nbr, w), 0.2))
+    assert abs(c.item() - orc.consensus_dist(got)) <= REL * orc.consensus_dist(got)
+
+
 # ------------------------------------------------------------------------- gradient producer
 def test_synth_grad_matches_oracle(psgd):
     for count in (1, 5, 4096, 100_003):

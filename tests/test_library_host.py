@@ -19,7 +19,7 @@ def test_library_exports_every_declared_symbol():
     with open(os.path.join(ROOT, "include", "psgd.h")) as f:
         text = re.sub(r"/\*.*?\*/", "", f.read(), flags=re.S)
     declared = sorted(set(re.findall(r"\b(psgd_[a-z0-9_]+)\s*\(", text)))
-    assert len(declared) >= 11
+    assert len(declared) >= 13
     for name in declared:
         assert hasattr(lib, name), name
     assert sorted(psgd.EXPORTS) == declared
@@ -104,6 +104,17 @@ def test_mix_step_argument_checks_need_no_device():
     assert lib.psgd_mix_step_cd(A, B, C, T1, T2, n, d, 0.1, 0, 0x3000004, None) == psgd.EALIGN
     assert lib.psgd_mix_step_cd(A, B, C, T1, T2, n, d, 0.1, 0, B + 8, None) == psgd.EALIAS
     assert lib.psgd_mix_step_cd_bf16g(A, A, C, T1, T2, n, d, 0.1, 1, 0x3000000, None) == psgd.EALIAS
+    ex = lib.psgd_mix_step_ex
+    # pitched rows: arrays may interleave (X rows at A + i*P, X_out rows right behind them) ...
+    P = 3 * d            # elements
+    assert ex(A, P, A + 4 * d, P, A + 8 * d, 2 * P, 1, T1, T2, n, d, 0.1, 0, None, None) in (psgd.OK, psgd.EHIP)
+    # ... but must not share bytes, pitches must cover a row, in-place needs equal pitches
+    assert ex(A, P, A + 4 * d - 4, P, C, d, 0, T1, T2, n, d, 0.1, 0, None, None) == psgd.EALIAS
+    assert ex(A, d - 1, B, d, C, d, 0, T1, T2, n, d, 0.1, 0, None, None) == psgd.EINVAL
+    assert ex(A, P, A, 2 * P, C, d, 0, T1, T2, n, d, 0.1, 0, None, None) == psgd.EALIAS
+    assert ex(A, P, A, P, C, d, 0, T1, T2, n, d, 0.1, 1, None, None) == psgd.EALIAS
+    assert ex(A, P, B, d, C, d, 2, T1, T2, n, d, 0.1, 0, None, None) == psgd.EINVAL
+    assert ex(A, P, A, P, C, d, 0, T1, T2, n, 0, 0.1, 0, None, None) == psgd.OK
     # an empty model is a no-op that needs no device either; in-place is legal in mode 0
     assert call(d=0) == psgd.OK
     assert call(O=A, d=0) == psgd.OK
@@ -121,6 +132,8 @@ def test_other_entry_points_argument_checks():
     assert lib.psgd_consensus_dist_async(A, 4, 10, None, None) == psgd.EINVAL
     assert lib.psgd_consensus_dist_async(A, 4, 10, A + 4, None) == psgd.EALIGN
     assert lib.psgd_consensus_dist_async(None, 4, 10, A, None) == psgd.EINVAL
+    assert lib.psgd_consensus_dist_ex(A, 5, 4, 10, A, None) == psgd.EINVAL      # pitch < d
+    assert lib.psgd_consensus_dist_ex(A, 50, 4, 10, None, None) == psgd.EINVAL
     assert lib.psgd_synth_grad(None, A, A, 10, 0.1, None) == psgd.EINVAL
     assert lib.psgd_synth_grad(A, A + 4096, A + 8, 10, 0.1, None) == psgd.EALIAS
     assert lib.psgd_synth_grad(A, A + 4096, A + 8192, -1, 0.1, None) == psgd.EINVAL
