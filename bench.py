@@ -85,9 +85,12 @@ def main():
                     help="separate mix and consensus kernels instead of the fused psgd_mix_step_cd")
     ap.add_argument("--in-place", action="store_true", help="mix in place instead of ping-pong buffers")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-placement", action="store_true",
-                    help="allocate X / X_out as separate tensors instead of probing one HBM pool for the windows "
-                         "with the best write rate (see paper_2002_01119_amd/placement.py)")
+    ap.add_argument("--layout", choices=["pitched", "probe", "dense"], default="pitched",
+                    help="where the arrays live in HBM: 'pitched' interleaves the rows of all arrays across most of "
+                         "the device (psgd_mix_step_ex), 'probe' keeps dense arrays but places X / X_out on the "
+                         "windows of one pool where the step runs fastest, 'dense' is one plain tensor per array")
+    ap.add_argument("--span-fraction", type=float, default=0.65,
+                    help="pitched layout: fraction of device memory the row slots are spread over")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="before the warm-up, run one plain device copy X -> X_out of known size (n*d*4 bytes read "
                          "and written); under rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE readings calibrate the "
@@ -116,41 +119,69 @@ def main():
     log("workload %s: n=%d d=%d G=%s steps=%d warmup=%d" % (wl.name, n, d, wl.g_dtype, K, W))
 
     # ---- resident inputs
-    if wl.g_dtype == "bf16":
-        Gs = [inp.device_normal_bf16((n, d), wl.sigma_g, wl.seed_g + i, dev) for i in range(2)]
-    else:
-        Gs = [inp.device_normal_f32((n, d), wl.sigma_g, wl.seed_g + i, dev) for i in range(2)]
     n_xbuf = 1 if args.in_place else (3 if wl.delay else 2)
-    placement, pool = None, None
-    if not args.no_placement:
+    gdt = torch.bfloat16 if wl.g_dtype == "bf16" else torch.float32
+    layout_report, pool, views = {"layout": args.layout}, None, None
+
+    def draw_g(i):
+        return (inp.device_normal_bf16 if wl.g_dtype == "bf16" else inp.device_normal_f32)(
+            (n, d), wl.sigma_g, wl.seed_g + i, dev)
+
+    if args.layout == "pitched":
+        # Rows of every array interleaved across most of the HBM (see placement.pitched_layout):
+        # slot i = [X_i | Y_i | (Xprev_i) | G0_i | G1_i | (noise_i)], slots `pitch` bytes apart.
+        from paper_2002_01119_amd import placement as plc
+        free, total_mem = torch.cuda.mem_get_info()
+        specs = [("X", torch.float32)] + ([] if args.in_place else [("Y", torch.float32)])
+        if wl.delay:
+            specs += [("Xprev", torch.float32), ("noise", torch.float32)]
+        specs += [("G0", gdt), ("G1", gdt)]
+        span = min(int(args.span_fraction * total_mem), free - (8 << 30))
+        try:
+            views, pool, pitch = plc.pitched_layout(n, d, specs, span, dev)
+            layout_report.update({"pitch_GB": pitch / 1e9, "span_GB": pool.numel() / 1e9,
+                                  "arrays": [s_[0] for s_ in specs]})
+            log("pitched layout: %d slots %.3f GB apart, pool %.1f GB" % (n, pitch / 1e9, pool.numel() / 1e9))
+        except torch.OutOfMemoryError:
+            log("pitched layout does not fit; falling back to dense tensors")
+            views, layout_report = None, {"layout": "dense (pitched did not fit)"}
+        if views is not None:
+            X = inp.fill_normal_rows_(views["X"], wl.sigma_x, wl.seed_x)
+            Y = X if args.in_place else views["Y"]
+            Gs = [inp.fill_normal_rows_(views["G%d" % i], wl.sigma_g, wl.seed_g + i) for i in range(2)]
+    elif args.layout == "probe":
         # X and X_out are rewritten every step: put them where this chip writes fastest
         from paper_2002_01119_amd import placement as plc
+        Gs = [draw_g(i) for i in range(2)]
         nbr0, w0 = psgd.build_mixing(wl.topology, n, wl.seed_perm, 0)
         extra = (n * d * 4 if wl.delay else 0) + (6 << 30)          # noise buffer + headroom
         try:
-            views, pool, placement = plc.place_replica_buffers(
+            wins, pool, rep = plc.place_replica_buffers(
                 n, d, n_xbuf, Gs[0], torch.from_numpy(nbr0).to(dev), torch.from_numpy(w0).to(dev),
                 reserve_bytes=extra, max_pool_bytes=12 * n * d * 4, log=log)
+            layout_report.update(rep)
+            views = {"X": wins[0]}
+            if not args.in_place:
+                views["Y"] = wins[1]
+            if wl.delay:
+                views["Xprev"] = wins[2]
+            X = inp.fill_normal_rows_(views["X"], wl.sigma_x, wl.seed_x)
+            Y = X if args.in_place else views["Y"]
         except (torch.OutOfMemoryError, RuntimeError) as e:
-            log("placement probe skipped (%s); falling back to separate allocations" % (str(e).splitlines()[0],))
-            views = None
-    else:
-        views = None
-    if views is not None:
-        X = views[0]
-        g = torch.Generator(device=dev)
-        g.manual_seed(wl.seed_x)
-        X.normal_(0.0, wl.sigma_x, generator=g)
-        Y = X if args.in_place else views[1]
-    else:
+            log("placement probe skipped (%s); falling back to dense tensors" % (str(e).splitlines()[0],))
+            views, layout_report = None, {"layout": "dense (probe did not fit)"}
+            del Gs
+    if views is None:
         X = inp.device_normal_f32((n, d), wl.sigma_x, wl.seed_x, dev)
         Y = X if args.in_place else torch.empty_like(X)
+        Gs = [draw_g(i) for i in range(2)]
     noise = None
     if wl.delay:                      # delay-by-one: G_k = c * X_{k-1} + noise, three X buffers
-        noise = inp.device_normal_f32((n, d), wl.sigma_g, wl.seed_g + 7, dev)
+        noise = views["noise"] if (views is not None and "noise" in views) else torch.empty((n, d), device=dev)
+        inp.fill_normal_rows_(noise, wl.sigma_g, wl.seed_g + 7)
     X_prev = None
     if wl.delay:
-        X_prev = views[2] if views is not None else torch.empty_like(X)
+        X_prev = views["Xprev"] if (views is not None and "Xprev" in views) else torch.empty((n, d), device=dev)
         X_prev.copy_(X)
     nbr_host = torch.empty((total, n, 3), dtype=torch.int32, pin_memory=True)
     w_host = torch.empty((total, n, 3), dtype=torch.float32, pin_memory=True)
@@ -251,7 +282,7 @@ def main():
             "delay_by_one": wl.delay, "consensus_every_step": not args.no_consensus,
             "consensus_fused_into_mix_kernel": fused,
             "in_place": bool(args.in_place),
-            "hbm_placement_probe": placement,
+            "hbm_layout": layout_report,
         },
         "roofline": {
             "kernel": "mix_step_kernel (with fused consensus statistics)" if fused else "mix_step_kernel",

@@ -188,6 +188,10 @@ int psgd_consensus_dist_ex(const float* X, int64_t ldx, int n, int64_t d, double
 int psgd_synth_grad(const float* X_prev, const float* noise, float* G,
                     int64_t count, float c, void* stream);
 
+/* psgd_synth_grad_ex - the same for [n, d] arrays whose rows are ld* (>= d) elements apart. */
+int psgd_synth_grad_ex(const float* X_prev, int64_t ldx, const float* noise, int64_t ldn,
+                       float* G, int64_t ldg, int n, int64_t d, float c, void* stream);
+
 /*
  * psgd_device_status - waits for the current device, then returns the sticky flag word that
  * kernels raise (bit 0: a mixing table held an entry outside [0, n) and the step wrote

@@ -520,6 +520,24 @@ __global__ __launch_bounds__(kThreads) void synth_grad_kernel(const float* __res
     }
 }
 
+// Row-pitched form: a lane owns one column group and walks the n rows.
+template <int VEC>
+__global__ __launch_bounds__(kThreads) void synth_grad_rows_kernel(const float* __restrict__ xp, int64_t ldx,
+                                                                   const float* __restrict__ noise, int64_t ldn,
+                                                                   float* __restrict__ g, int64_t ldg, int n,
+                                                                   int64_t d, float c) {
+    const Cols<VEC> tag{};
+    const int64_t ncg = d / VEC;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t cg = (int64_t)blockIdx.x * kThreads + threadIdx.x; cg < ncg; cg += stride) {
+        const int64_t col = cg * VEC;
+#pragma unroll 4
+        for (int r = 0; r < n; ++r)
+            st_x(g + (int64_t)r * ldg + col,
+                 vfma(c, ld_x(xp + (int64_t)r * ldx + col, tag), ld_x(noise + (int64_t)r * ldn + col, tag)));
+    }
+}
+
 // ---------------------------------------------------------------------------------------
 // Host helpers.
 // ---------------------------------------------------------------------------------------
@@ -829,6 +847,39 @@ int psgd_synth_grad(const float* X_prev, const float* noise, float* G, int64_t c
                        noise, G, count, c, vec4);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "synth_grad_kernel");
+    return PSGD_OK;
+}
+
+int psgd_synth_grad_ex(const float* X_prev, int64_t ldx, const float* noise, int64_t ldn, float* G, int64_t ldg,
+                       int n, int64_t d, float c, void* stream) {
+    using namespace psgd;
+    clear_error();
+    if (!X_prev || !noise || !G) return fail(PSGD_EINVAL, "psgd_synth_grad_ex: null pointer");
+    if (n < 1 || n > PSGD_MAX_N || d < 0) return fail(PSGD_EINVAL, "psgd_synth_grad_ex: n=%d d=%lld", n, (long long)d);
+    if (n > 1 && (ldx < d || ldn < d || ldg < d)) return fail(PSGD_EINVAL, "psgd_synth_grad_ex: a row pitch is smaller than d");
+    if (n == 1) ldx = ldn = ldg = d;
+    if (!aligned_to(X_prev, 4) || !aligned_to(noise, 4) || !aligned_to(G, 4))
+        return fail(PSGD_EALIGN, "psgd_synth_grad_ex: pointer not 4-byte aligned");
+    const int64_t ldmax = ldx > ldn ? (ldx > ldg ? ldx : ldg) : (ldn > ldg ? ldn : ldg);
+    if (ldmax > 0 && (int64_t)n > INT64_MAX / 8 / ldmax) return fail(PSGD_EINVAL, "psgd_synth_grad_ex: n * pitch overflows");
+    const size_t row = (size_t)d * sizeof(float);
+    if (rows_overlap(G, ldg * 4, row, X_prev, ldx * 4, row, n) || rows_overlap(G, ldg * 4, row, noise, ldn * 4, row, n))
+        return fail(PSGD_EALIAS, "psgd_synth_grad_ex: G overlaps an input");
+    if (d == 0) return PSGD_OK;
+    DeviceInfo* di = nullptr;
+    if (int rc = device_info(&di, false)) return rc;
+    const bool vec4 = d % 4 == 0 && ldx % 4 == 0 && ldn % 4 == 0 && ldg % 4 == 0 && aligned_to(X_prev, 16) &&
+                      aligned_to(noise, 16) && aligned_to(G, 16);
+    const int grid = persistent_grid(*di, vec4 ? d / 4 : d, 8);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (vec4)
+        hipLaunchKernelGGL(synth_grad_rows_kernel<4>, dim3(grid), dim3(kThreads), 0, s, X_prev, ldx, noise, ldn, G, ldg,
+                           n, d, c);
+    else
+        hipLaunchKernelGGL(synth_grad_rows_kernel<1>, dim3(grid), dim3(kThreads), 0, s, X_prev, ldx, noise, ldn, G, ldg,
+                           n, d, c);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "synth_grad_rows_kernel");
     return PSGD_OK;
 }
 

@@ -105,6 +105,20 @@ def device_normal_bf16(shape, sigma, seed, device="cuda:0"):
     return t
 
 
+def fill_normal_rows_(t, sigma, seed):
+    """Fill an [n, d] device tensor (any row pitch, fp32 or bf16) with N(0, sigma^2) one row at
+    a time, so no temporary larger than a row is needed.  bf16 rows are drawn in fp32 and
+    rounded once."""
+    import torch
+    g = torch.Generator(device=t.device)
+    g.manual_seed(seed)
+    tmp = torch.empty(t.shape[1], dtype=torch.float32, device=t.device)
+    for i in range(t.shape[0]):
+        tmp.normal_(0.0, sigma, generator=g)
+        t[i].copy_(tmp)
+    return t
+
+
 def bf16_tensor_bits(t):
     """uint16 bit patterns (numpy) of a bfloat16 torch tensor."""
     import torch

@@ -17,6 +17,28 @@ import torch
 from . import psgd
 
 
+def pitched_layout(n, d, specs, span_bytes, device):
+    """Interleave the rows of several [n, d] arrays in ONE pool so that every array spans
+    `span_bytes` of device memory: slot i (at i * pitch) holds row i of each array back to
+    back.  `specs` is a list of (name, torch dtype).  Returns (dict name -> [n, d] strided view,
+    pool tensor, pitch in bytes).  Row starts are 4 KB aligned."""
+    def up(v, a):
+        return (v + a - 1) // a * a
+    offs, cur = {}, 0
+    for name, dt in specs:
+        offs[name] = cur
+        cur += up(d * torch.empty((), dtype=dt).element_size(), 4096)
+    pitch = max(cur, (span_bytes // max(n, 1)) // 4096 * 4096)
+    pool_bytes = (n - 1) * pitch + cur
+    pool = torch.empty(pool_bytes, dtype=torch.uint8, device=device)
+    views = {}
+    for name, dt in specs:
+        es = torch.empty((), dtype=dt).element_size()
+        flat = pool.view(dt)
+        views[name] = flat.as_strided((n, d), (pitch // es, 1), offs[name] // es)
+    return views, pool, pitch
+
+
 def _window(pool, offset, n, d):
     return pool[offset:offset + n * d * 4].view(torch.float32).view(n, d)
 

@@ -23,7 +23,7 @@ _lib = None
 EXPORTS = (
     "psgd_build_mixing", "psgd_mix_step", "psgd_mix_step_bf16g", "psgd_mix_step_cd",
     "psgd_mix_step_cd_bf16g", "psgd_mix_step_ex", "psgd_consensus_dist", "psgd_consensus_dist_ex",
-    "psgd_consensus_dist_async", "psgd_synth_grad", "psgd_device_status", "psgd_last_error",
+    "psgd_consensus_dist_async", "psgd_synth_grad", "psgd_synth_grad_ex", "psgd_device_status", "psgd_last_error",
     "psgd_version",
 )
 
@@ -70,6 +70,9 @@ def load(reload=False):
     lib.psgd_consensus_dist_async.argtypes = [vp, ctypes.c_int, ctypes.c_int64, vp, vp]
     lib.psgd_synth_grad.restype = ctypes.c_int
     lib.psgd_synth_grad.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_float, vp]
+    lib.psgd_synth_grad_ex.restype = ctypes.c_int
+    lib.psgd_synth_grad_ex.argtypes = [vp, ctypes.c_int64, vp, ctypes.c_int64, vp, ctypes.c_int64, ctypes.c_int,
+                                       ctypes.c_int64, ctypes.c_float, vp]
     lib.psgd_device_status.restype = ctypes.c_int
     lib.psgd_device_status.argtypes = [ctypes.c_int]
     lib.psgd_last_error.restype = ctypes.c_char_p
@@ -191,14 +194,19 @@ def consensus_dist_async(X, out, stream=None):
 
 
 def synth_grad(X_prev, noise, G, c, stream=None):
-    """Enqueue G = c * X_prev + noise (fp32, elementwise) for the delay-by-one workload."""
-    if X_prev.numel() != noise.numel() or X_prev.numel() != G.numel():
-        raise ValueError("X_prev, noise and G must have the same number of elements")
-    for t in (X_prev, noise, G):
-        if not t.is_contiguous():
-            raise ValueError("tensors must be contiguous")
-    _check(load().psgd_synth_grad(X_prev.data_ptr(), noise.data_ptr(), G.data_ptr(), X_prev.numel(),
-                                  float(c), _stream_handle(stream)))
+    """Enqueue G = c * X_prev + noise (fp32, elementwise) for the delay-by-one workload.
+    Contiguous tensors of any shape, or [n, d] tensors with pitched rows."""
+    if X_prev.shape != noise.shape or X_prev.shape != G.shape:
+        raise ValueError("X_prev, noise and G must have one shape")
+    if X_prev.is_contiguous() and noise.is_contiguous() and G.is_contiguous():
+        _check(load().psgd_synth_grad(X_prev.data_ptr(), noise.data_ptr(), G.data_ptr(), X_prev.numel(),
+                                      float(c), _stream_handle(stream)))
+        return
+    n, d, ldx = _rows_cols_pitch(X_prev)
+    _, _, ldn = _rows_cols_pitch(noise)
+    _, _, ldg = _rows_cols_pitch(G)
+    _check(load().psgd_synth_grad_ex(X_prev.data_ptr(), ldx, noise.data_ptr(), ldn, G.data_ptr(), ldg, n, d,
+                                     float(c), _stream_handle(stream)))
 
 
 def device_status(clear=True):

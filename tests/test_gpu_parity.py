@@ -406,6 +406,22 @@ def test_synth_grad_matches_oracle(psgd):
         assert_close(G.cpu().numpy(), want, rel=2.0 ** -23)
 
 
+def test_synth_grad_pitched_rows(psgd):
+    n, d, pitch = 8, 1030, 4096
+    pool = torch.zeros(n * pitch, device="cuda:0")
+    Xp = pool.as_strided((n, d), (pitch, 1), 0)
+    Z = pool.as_strided((n, d), (pitch, 1), d)
+    G = pool.as_strided((n, d), (pitch, 1), 2 * d)
+    Xh = inp.host_normal_f32((n, d), 0.02, 93)
+    Zh = inp.host_normal_f32((n, d), 1e-3, 94)
+    Xp.copy_(dev(Xh))
+    Z.copy_(dev(Zh))
+    psgd.synth_grad(Xp, Z, G, 0.01)
+    torch.cuda.synchronize()
+    assert_close(G.cpu().numpy(), orc.synth_grad(Xh, Zh, 0.01), rel=2.0 ** -23)
+    assert np.array_equal(Xp.cpu().numpy(), Xh) and np.array_equal(Z.cpu().numpy(), Zh)
+
+
 # ------------------------------------------------------------------------- short trajectories
 @pytest.mark.parametrize("topo", [orc.TOPO_RING, orc.TOPO_RAND_RING])
 def test_cfg1_full_trajectory_every_element(psgd, topo):

@@ -19,7 +19,7 @@ def test_library_exports_every_declared_symbol():
     with open(os.path.join(ROOT, "include", "psgd.h")) as f:
         text = re.sub(r"/\*.*?\*/", "", f.read(), flags=re.S)
     declared = sorted(set(re.findall(r"\b(psgd_[a-z0-9_]+)\s*\(", text)))
-    assert len(declared) >= 13
+    assert len(declared) >= 14
     for name in declared:
         assert hasattr(lib, name), name
     assert sorted(psgd.EXPORTS) == declared
@@ -134,6 +134,8 @@ def test_other_entry_points_argument_checks():
     assert lib.psgd_consensus_dist_async(None, 4, 10, A, None) == psgd.EINVAL
     assert lib.psgd_consensus_dist_ex(A, 5, 4, 10, A, None) == psgd.EINVAL      # pitch < d
     assert lib.psgd_consensus_dist_ex(A, 50, 4, 10, None, None) == psgd.EINVAL
+    assert lib.psgd_synth_grad_ex(A, 5, A + 4096, 50, A + 8192, 50, 4, 10, 0.1, None) == psgd.EINVAL
+    assert lib.psgd_synth_grad_ex(A, 50, A + 4096, 50, A + 220, 50, 4, 10, 0.1, None) == psgd.EALIAS
     assert lib.psgd_synth_grad(None, A, A, 10, 0.1, None) == psgd.EINVAL
     assert lib.psgd_synth_grad(A, A + 4096, A + 8, 10, 0.1, None) == psgd.EALIAS
     assert lib.psgd_synth_grad(A, A + 4096, A + 8192, -1, 0.1, None) == psgd.EINVAL
