@@ -92,9 +92,8 @@ def main():
     ap.add_argument("--span-fraction", type=float, default=0.65,
                     help="pitched layout: fraction of device memory the row slots are spread over")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="before the warm-up, run one plain device copy X -> X_out of known size (n*d*4 bytes read "
-                         "and written); under rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE readings calibrate the "
-                         "mix kernel's")
+                    help="before the warm-up, run a plain dense device copy of known size (printed); under "
+                         "rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE readings calibrate the mix kernel's")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs all learners on ONE GPU (no collectives); --gpus %d is not "
@@ -218,16 +217,21 @@ def main():
             X, Y = Y, X
 
     with torch.cuda.stream(stream):
-        if args.calibrate_copy and not args.in_place:
-            Y.copy_(X)
+        if args.calibrate_copy:
+            cal_bytes = min(12_800_000_000, torch.cuda.mem_get_info()[0] // 3) // 4096 * 4096
+            ca = torch.zeros(cal_bytes, dtype=torch.uint8, device=dev)
+            cb = torch.empty_like(ca)
+            cb.copy_(ca)
             t_c0, t_c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             t_c0.record(stream)
-            Y.copy_(X)
+            cb.copy_(ca)
             t_c1.record(stream)
             torch.cuda.synchronize()
             cms = t_c0.elapsed_time(t_c1)
-            log("plain device copy X -> X_out: %.3f ms -> %.1f GB/s (%.1f %% of peak)"
-                % (cms, 8 * n * d / cms / 1e6, 8 * n * d / cms / 1e6 / HBM_PEAK_GBS * 100))
+            log("calibration: plain dense device copy of %d bytes (= %d KiB read and as many written): %.3f ms -> "
+                "%.1f GB/s (%.1f %% of peak)" % (cal_bytes, cal_bytes // 1024, cms, 2 * cal_bytes / cms / 1e6,
+                                                 2 * cal_bytes / cms / 1e6 / HBM_PEAK_GBS * 100))
+            del ca, cb
         for k in range(W):
             one_step(k)
         torch.cuda.synchronize()
