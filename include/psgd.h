@@ -145,11 +145,10 @@ int psgd_mix_step_cd_bf16g(const float* X, float* X_out, const uint16_t* G_bf16,
  * path needs d and all three pitches to be multiples of 4.
  *
  * Why pitches: (1) a column shard of a wider array is such a view; (2) placement.  On
- * MI355X a kernel that streams rows which all lie in one third of the 288 GB address range
- * reaches about 63 % of the HBM peak on this step, while rows spread over two or three
- * thirds reach 75-77 %: an [n, d] array allocated densely is a few tens of GB and sits in
- * one third, the same array with its rows pitched a few GB apart (other arrays' rows in
- * between) spans the device.
+ * MI355X this step was measured at 63-66 % of the HBM peak when each array is one dense
+ * block of a few tens of GB, and at 74-76 % when the rows of every array are pitched a few
+ * GB apart (other arrays' rows in between) so that the rows in flight cover most of the
+ * device's address range.
  */
 int psgd_mix_step_ex(const float* X, int64_t ldx, float* X_out, int64_t ldo,
                      const void* G, int64_t ldg, int g_is_bf16,
