@@ -86,21 +86,37 @@ def expected_consensus_d1d(Ts, d, sigma_x, sigma_g, lr, c):
     return out
 
 
-def run_workload(psgd, wl, topo, steps=None):
+def run_workload(psgd, wl, topo, steps=None, layout="dense"):
     """Runs the workload on the GPU at full size and the oracle on sampled columns.
+    layout "pitched" is the benchmark's: rows of all arrays interleaved across 65 % of the
+    device memory (row-pitched entry points); "dense" is one plain tensor per array.
     Returns (consensus distances after each step, dense T list, final device X)."""
     steps = steps or wl.steps
     n, d = wl.n, wl.d
     cols = inp.sample_columns(d, SAMPLE, seed=wl.seed_x)
     cols_t = torch.from_numpy(cols).to("cuda:0")
-    X = inp.device_normal_f32((n, d), wl.sigma_x, wl.seed_x)
-    Y = torch.empty_like(X)
+    gdt = torch.bfloat16 if wl.g_dtype == "bf16" else torch.float32
+    if layout == "pitched":
+        from paper_2002_01119_amd import placement as plc
+        specs = [("X", torch.float32), ("Y", torch.float32), ("G", gdt)]
+        if wl.delay:
+            specs += [("Xprev", torch.float32), ("noise", torch.float32)]
+        total_mem = torch.cuda.mem_get_info()[1]
+        views, pool, pitch = plc.pitched_layout(n, d, specs, int(0.65 * total_mem), "cuda:0")
+        assert views["X"].stride(0) * 4 == pitch and pitch > d * 4
+        X, Y, Gbuf = views["X"], views["Y"], views["G"]
+        X.copy_(inp.device_normal_f32((n, d), wl.sigma_x, wl.seed_x))
+    else:
+        views, Gbuf = None, None
+        X = inp.device_normal_f32((n, d), wl.sigma_x, wl.seed_x)
+        Y = torch.empty_like(X)
     Xo = pull(X, cols_t).astype(np.float64)
     Xo_prev = Xo
     if wl.delay:
-        noise = torch.empty_like(X)
-        G = torch.empty_like(X)
-        X_prev = X.clone()              # X_{-1} := X_0
+        noise = views["noise"] if views else torch.empty_like(X)
+        G = Gbuf if views else torch.empty_like(X)
+        X_prev = views["Xprev"] if views else torch.empty_like(X)
+        X_prev.copy_(X)                 # X_{-1} := X_0
     gen = torch.Generator(device="cuda:0")
     gen.manual_seed(wl.seed_g)
     # A free-running trajectory is compared relative to the largest magnitude it has held:
@@ -122,11 +138,12 @@ def run_workload(psgd, wl, topo, steps=None):
             Go = orc.synth_grad(Xo_prev, pull(noise, cols_t), wl.grad_pull)
             # the producer's own rounding: G is an fp32 buffer
             assert_close(pull(G, cols_t), Go, rel=2.0 ** -23)
-        elif wl.g_dtype == "bf16":
-            G = inp.device_normal_bf16((n, d), wl.sigma_g, wl.seed_g * 1000 + k)
-            Go = pull(G, cols_t)
         else:
-            G = inp.device_normal_f32((n, d), wl.sigma_g, wl.seed_g * 1000 + k)
+            draw = inp.device_normal_bf16 if wl.g_dtype == "bf16" else inp.device_normal_f32
+            G = draw((n, d), wl.sigma_g, wl.seed_g * 1000 + k)
+            if Gbuf is not None:
+                Gbuf.copy_(G)
+                G = Gbuf
             Go = pull(G, cols_t)
         if k % 2 == 0:      # alternate the fused entry point with the two separate calls
             psgd.mix_step(X, Y, G, dev(nbr), dev(w), wl.lr, delay_mode=1 if wl.delay else 0,
@@ -154,6 +171,9 @@ def run_workload(psgd, wl, topo, steps=None):
     assert psgd.device_status() == 0
     cdist = c_out.cpu().numpy()
     # the consensus kernel on the sampled slice, against the oracle on the same bits
+    psgd.consensus_dist_async(X, c_chk)             # separate kernel on the final layout
+    torch.cuda.synchronize()
+    assert abs(c_chk.item() - cdist[-1]) <= 1e-9 * cdist[-1]
     Xs = X.index_select(1, cols_t).contiguous()
     c_slice = psgd.consensus_dist(Xs)
     c_ref = orc.consensus_dist(Xs.cpu().numpy())
@@ -174,7 +194,7 @@ def test_cfg2_randomized_vs_fixed_ring(psgd):
     wl = inp.workload(2)
     out = {}
     for topo in (orc.TOPO_RAND_RING, orc.TOPO_RING):
-        cdist, Ts, _ = run_workload(psgd, wl, topo)
+        cdist, Ts, _ = run_workload(psgd, wl, topo, layout="pitched" if topo == orc.TOPO_RAND_RING else "dense")
         check_against_expectation(cdist, expected_consensus(Ts, wl.d, wl.sigma_x, wl.sigma_g, wl.lr),
                                   wl.d, wl.n, "cfg2 topo %d" % topo)
         out[topo] = cdist
@@ -190,7 +210,7 @@ def test_cfg3_contraction_vs_spectral_gap(psgd):
     rho = orc.spectral_rho(orc.ring_matrix(wl.n))
     assert abs(rho - (1 / 3 + 2 / 3 * math.cos(2 * math.pi / wl.n))) < 1e-12
     for topo in (orc.TOPO_RING, orc.TOPO_RAND_RING):
-        cdist, Ts, _ = run_workload(psgd, wl, topo)
+        cdist, Ts, _ = run_workload(psgd, wl, topo, layout="pitched" if topo == orc.TOPO_RAND_RING else "dense")
         check_against_expectation(cdist, expected_consensus(Ts, wl.d, wl.sigma_x, wl.sigma_g, wl.lr),
                                   wl.d, wl.n, "cfg3 topo %d" % topo)
         # per-step contraction sqrt(C_{k+1} / C_k) never exceeds rho while the gradient
@@ -206,29 +226,49 @@ def test_cfg3_contraction_vs_spectral_gap(psgd):
 
 def test_cfg4_delay_by_one(psgd):
     wl = inp.workload(4)
-    cdist, Ts, _ = run_workload(psgd, wl, orc.TOPO_RAND_RING)
+    cdist, Ts, _ = run_workload(psgd, wl, orc.TOPO_RAND_RING, layout="pitched")
     expect = expected_consensus_d1d(Ts, wl.d, wl.sigma_x, wl.sigma_g, wl.lr, wl.grad_pull)
     check_against_expectation(cdist, expect, wl.d, wl.n, "cfg4")
     torch.cuda.empty_cache()
 
 
 def test_cfg5_bf16_gradients_full_size(psgd):
+    """The benchmark's configuration: workload 5 in the row-pitched layout, fused distance."""
     wl = inp.workload(5)
-    cdist, Ts, X = run_workload(psgd, wl, orc.TOPO_RAND_RING)
+    cdist, Ts, X = run_workload(psgd, wl, orc.TOPO_RAND_RING, layout="pitched")
+    assert X.stride(0) > wl.d
     check_against_expectation(cdist, expected_consensus(Ts, wl.d, wl.sigma_x, wl.sigma_g, wl.lr),
                               wl.d, wl.n, "cfg5")
     assert abs(cdist[-1] / 23.26 - 1) < 0.05
     # full-size launch of the consensus kernel on an array with an exact closed form:
     # X[i, j] = i gives d n (n^2 - 1) / 12 (all intermediate values are integers in fp64)
     X.copy_(torch.arange(wl.n, dtype=torch.float32, device="cuda:0")[:, None].expand(wl.n, wl.d))
-    assert psgd.consensus_dist(X) == wl.d * wl.n * (wl.n ** 2 - 1) / 12
+    c = torch.zeros(1, dtype=torch.float64, device="cuda:0")
+    psgd.consensus_dist_async(X, c)
+    torch.cuda.synchronize()
+    assert c.item() == wl.d * wl.n * (wl.n ** 2 - 1) / 12
     # and in place at full size: mixing the constant-per-row array with lr = 0 on a fixed ring
     nbr, w = psgd.build_mixing(psgd.TOPO_RING, wl.n)
     G = torch.zeros(wl.n, wl.d, dtype=torch.bfloat16, device="cuda:0")
-    psgd.mix_step(X, X, G, dev(nbr), dev(w), 0.0)
+    psgd.mix_step(X, X, G, dev(nbr), dev(w), 0.0, cdist_out=c)
     cols_t = torch.from_numpy(inp.sample_columns(wl.d, SAMPLE, 5)).to("cuda:0")
     got = pull(X, cols_t)
     rows = np.arange(wl.n, dtype=np.float32)[:, None].repeat(cols_t.numel(), axis=1)
-    assert_close(got, orc.mix_step(rows, np.zeros_like(rows), orc.densify(nbr, w), 0.0))
+    want = orc.mix_step(rows, np.zeros_like(rows), orc.densify(nbr, w), 0.0)
+    assert_close(got, want)
+    assert abs(c.item() - orc.consensus_dist(want) * wl.d / cols_t.numel()) <= 1e-5 * c.item()
     del X, G
+    torch.cuda.empty_cache()
+
+
+def test_cfg5_dense_layout_full_size(psgd):
+    """The same workload as plain dense tensors (the entry points the baseline names), 4 steps."""
+    wl = inp.workload(5)
+    cdist, Ts, X = run_workload(psgd, wl, orc.TOPO_RAND_RING, steps=4, layout="dense")
+    assert X.is_contiguous()
+    check_against_expectation(cdist, expected_consensus(Ts, wl.d, wl.sigma_x, wl.sigma_g, wl.lr),
+                              wl.d, wl.n, "cfg5 dense")
+    X.copy_(torch.arange(wl.n, dtype=torch.float32, device="cuda:0")[:, None].expand(wl.n, wl.d))
+    assert psgd.consensus_dist(X) == wl.d * wl.n * (wl.n ** 2 - 1) / 12
+    del X
     torch.cuda.empty_cache()
