@@ -84,6 +84,9 @@ def main():
     ap.add_argument("--unfused", action="store_true",
                     help="separate mix and consensus kernels instead of the fused psgd_mix_step_cd")
     ap.add_argument("--in-place", action="store_true", help="mix in place instead of ping-pong buffers")
+    ap.add_argument("--global-average", action="store_true",
+                    help="mix with T_u = (1/n) 1 1^T (psgd_mix_full: S-PSGD / the paper's own D1D-PSGD) instead of "
+                         "the workload's ring table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layout", choices=["pitched", "probe", "dense"], default="pitched",
                     help="where the arrays live in HBM: 'pitched' interleaves the rows of all arrays across most of "
@@ -205,8 +208,12 @@ def main():
             psgd.synth_grad(X_prev, noise, G, wl.grad_pull, stream=stream)
         fused = not (args.unfused or args.no_consensus)
         ev0[k].record(stream)
-        psgd.mix_step(X, Y, G, nbr_dev[k], w_dev[k], wl.lr, delay_mode=1 if wl.delay else 0, stream=stream,
-                      cdist_out=cdist[k:k + 1] if fused else None)
+        if args.global_average:
+            psgd.mix_full(X, Y, G, wl.lr, delay_mode=1 if wl.delay else 0, stream=stream,
+                          cdist_out=cdist[k:k + 1] if fused else None)
+        else:
+            psgd.mix_step(X, Y, G, nbr_dev[k], w_dev[k], wl.lr, delay_mode=1 if wl.delay else 0, stream=stream,
+                          cdist_out=cdist[k:k + 1] if fused else None)
         ev1[k].record(stream)
         if not (fused or args.no_consensus):
             psgd.consensus_dist_async(Y, cdist[k:k + 1], stream=stream)
@@ -282,17 +289,19 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": wl.name, "n": n, "d": d, "g_dtype": wl.g_dtype,
-            "topology": {0: "ring", 1: "rand_ring"}[wl.topology], "lr": wl.lr,
+            "topology": "full (T_u)" if args.global_average else {0: "ring", 1: "rand_ring"}[wl.topology],
+            "lr": wl.lr,
             "delay_by_one": wl.delay, "consensus_every_step": not args.no_consensus,
             "consensus_fused_into_mix_kernel": fused,
             "in_place": bool(args.in_place),
             "hbm_layout": layout_report,
         },
         "roofline": {
-            "kernel": "mix_step_kernel (with fused consensus statistics)" if fused else "mix_step_kernel",
+            "kernel": ("mix_full_kernel" if args.global_average else "mix_step_kernel")
+                      + (" (with fused consensus statistics)" if fused else ""),
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
+            "traffic": None if args.global_average else MEASURED_TRAFFIC_BYTES.get(wl.name),
             "algorithmic_bytes_per_launch": mix_bytes, "avg_launch_ms": mix_avg,
         },
         "mix_updates_per_s": n * d / (mix_avg * 1e-3),

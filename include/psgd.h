@@ -36,7 +36,8 @@ extern "C" {
 /* Mixing topologies (Sec. 3). */
 enum {
     PSGD_TOPO_RING = 0,      /* fixed ring T_0: weights 1/3 on self and both cyclic neighbours (Eq. 3) */
-    PSGD_TOPO_RAND_RING = 1  /* T_tau = P^T T_0 P with a fresh seeded permutation per step (Eq. 8)     */
+    PSGD_TOPO_RAND_RING = 1, /* T_tau = P^T T_0 P with a fresh seeded permutation per step (Eq. 8)     */
+    PSGD_TOPO_FULL = 2       /* T_u = (1/L) 1 1^T: no table, applied by psgd_mix_full                  */
 };
 
 enum { PSGD_DEG = 3 };       /* slots per table row: self, left, right */
@@ -66,7 +67,7 @@ typedef enum {
  *
  *   nbr  host, int32 [n * 3], written        w  host, float [n * 3], written
  * Host only; touches no device.  Errors: PSGD_EINVAL (null pointer, n < 1 or
- * n > PSGD_MAX_N, unknown topology).
+ * n > PSGD_MAX_N, unknown topology, or PSGD_TOPO_FULL, which has no 3-slot table).
  */
 int psgd_build_mixing(int topology, int n, uint64_t seed, uint64_t step,
                       int32_t* nbr, float* w);
@@ -154,6 +155,21 @@ int psgd_mix_step_ex(const float* X, int64_t ldx, float* X_out, int64_t ldo,
                      const void* G, int64_t ldg, int g_is_bf16,
                      const int32_t* nbr, const float* w,
                      int n, int64_t d, float lr, int delay_mode, double* cdist_out, void* stream);
+
+/*
+ * psgd_mix_full - the step with global averaging, T = T_u = (1/L) 1 1^T:
+ *         X_out[i, :] = (1/n) sum_j X[j, :]  -  lr * G[i, :].
+ * This is S-PSGD's mixing matrix (Sec. 2) and the one D1D-PSGD realises with an allreduce
+ * divided by L (Sec. 4, Eq. 13); with delay_mode 1 and gradients taken one iterate earlier
+ * (Eq. 14) it is the paper's delay-by-one update.  No table is needed.
+ *
+ * Arguments, pitches, gradient type, in-place rule, optional cdist_out, errors and
+ * asynchrony are those of psgd_mix_step_ex.  Per element: the column sum is accumulated in
+ * fp64 over rows 0..n-1, mean = (float)(sum / n), out = fma(-lr, g, mean).
+ */
+int psgd_mix_full(const float* X, int64_t ldx, float* X_out, int64_t ldo,
+                  const void* G, int64_t ldg, int g_is_bf16,
+                  int n, int64_t d, float lr, int delay_mode, double* cdist_out, void* stream);
 
 /*
  * psgd_consensus_dist - sum_i || x_i - xbar ||^2 with xbar the mean of the n rows of X:

@@ -448,6 +448,79 @@ __global__ __launch_bounds__(kThreads) void mix_step_kernel(const float* X, floa
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Global averaging, T_u = (1/n) 1 1^T (Sec. 2: S-PSGD; Sec. 4, Eq. 13: D1D-PSGD's allreduce / L):
+//     X_out[i,:] = mean_j X[j,:] - lr * G[i,:].
+// A lane owns a column group: first sweep sums its n rows (fp64, so the mean carries one
+// fp32 rounding whatever n is), second sweep reads G and writes the n outputs.  All of the
+// lane's X loads precede its first store, so X_out may alias X.  Same bytes as the ring step.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void add_to(double* s, float x) { s[0] += (double)x; }
+__device__ __forceinline__ void add_to(double* s, f32x4 x) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) s[k] += (double)x[k];
+}
+__device__ __forceinline__ float mean_of(const double* s, double inv_n, Cols<1>) { return (float)(s[0] * inv_n); }
+__device__ __forceinline__ f32x4 mean_of(const double* s, double inv_n, Cols<4>) {
+    return (f32x4){(float)(s[0] * inv_n), (float)(s[1] * inv_n), (float)(s[2] * inv_n), (float)(s[3] * inv_n)};
+}
+
+template <int VEC, typename GT, bool CD>
+__global__ __launch_bounds__(kThreads) void mix_full_kernel(const float* X, float* Xout, const GT* __restrict__ G,
+                                                            int n, int64_t d, Pitch ld, float neg_lr,
+                                                            double* __restrict__ partials) {
+    typedef typename Cols<VEC>::T V;
+    const Cols<VEC> tag{};
+    __shared__ double lds4[4];
+    const int64_t ncg = d / VEC;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    const double inv_n = 1.0 / (double)n;
+    double total = 0.0;
+    for (int64_t cg = (int64_t)blockIdx.x * kThreads + threadIdx.x; cg < ncg; cg += stride) {
+        const int64_t col = cg * VEC;
+        const float* xc = X + col;
+        const GT* gc = G + col;
+        float* oc = Xout + col;
+        double sum[VEC];
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) sum[k] = 0.0;
+        int r = 0;
+        for (; r + kUnroll <= n; r += kUnroll) {
+            V xs[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) xs[u] = ld_x(xc + (int64_t)(r + u) * ld.x, tag);
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) add_to(sum, xs[u]);
+        }
+        for (; r < n; ++r) add_to(sum, ld_x(xc + (int64_t)r * ld.x, tag));
+        const V mean = mean_of(sum, inv_n, tag);
+        ColStats<VEC> stats;
+        if (CD) stats.reset();
+        r = 0;
+        for (; r + kUnroll <= n; r += kUnroll) {
+            V gs[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) gs[u] = ld_g(gc + (int64_t)(r + u) * ld.g, tag);
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const V out = vfma(neg_lr, gs[u], mean);
+                st_x(oc + (int64_t)(r + u) * ld.o, out);
+                if (CD) stats.add(out);
+            }
+        }
+        for (; r < n; ++r) {
+            const V out = vfma(neg_lr, ld_g(gc + (int64_t)r * ld.g, tag), mean);
+            st_x(oc + (int64_t)r * ld.o, out);
+            if (CD) stats.add(out);
+        }
+        if (CD) total += stats.result(inv_n);
+    }
+    if (CD) {
+        const double bs = block_sum(total, lds4);
+        if (threadIdx.x == 0) partials[blockIdx.x] = bs;
+    }
+}
+
 // Consensus-distance kernels (the per-column arithmetic is defined above the ring walk).
 template <int VEC>
 __global__ __launch_bounds__(kThreads) void consensus_partial_kernel(const float* __restrict__ X, int n,
@@ -713,6 +786,69 @@ int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
     return PSGD_OK;
 }
 
+template <typename GT>
+int mix_full_impl(const char* name, const float* X, int64_t ldx, float* X_out, int64_t ldo, const GT* G, int64_t ldg,
+                  int n, int64_t d, float lr, int delay_mode, double* cd_out, void* stream) {
+    clear_error();
+    const bool want_cd = cd_out != nullptr;
+    if (!X || !X_out || !G) return fail(PSGD_EINVAL, "%s: null pointer", name);
+    if (n < 1 || n > PSGD_MAX_N) return fail(PSGD_EINVAL, "%s: n=%d outside 1..%d", name, n, (int)PSGD_MAX_N);
+    if (d < 0) return fail(PSGD_EINVAL, "%s: d=%lld is negative", name, (long long)d);
+    if (delay_mode != 0 && delay_mode != 1) return fail(PSGD_EINVAL, "%s: delay_mode=%d", name, delay_mode);
+    if (n > 1 && (ldx < d || ldo < d || ldg < d))
+        return fail(PSGD_EINVAL, "%s: a row pitch is smaller than d=%lld", name, (long long)d);
+    if (n == 1) ldx = ldo = ldg = d;
+    if (!aligned_to(X, 4) || !aligned_to(X_out, 4) || !aligned_to(G, sizeof(GT)) || (want_cd && !aligned_to(cd_out, 8)))
+        return fail(PSGD_EALIGN, "%s: pointer not aligned to its element size", name);
+    const int64_t ldmax = ldx > ldo ? (ldx > ldg ? ldx : ldg) : (ldo > ldg ? ldo : ldg);
+    if (ldmax > 0 && (int64_t)n > INT64_MAX / 8 / ldmax) return fail(PSGD_EINVAL, "%s: n * pitch overflows", name);
+    const size_t xrow = (size_t)d * sizeof(float), grow = (size_t)d * sizeof(GT);
+    const int64_t bx = ldx * (int64_t)sizeof(float), bo = ldo * (int64_t)sizeof(float), bg = ldg * (int64_t)sizeof(GT);
+    if (static_cast<const void*>(X) == static_cast<const void*>(X_out) && ldx == ldo) {
+        if (delay_mode == 1)
+            return fail(PSGD_EALIAS, "%s: delay-by-one keeps X read-only, X_out must be another buffer", name);
+    } else if (rows_overlap(X, bx, xrow, X_out, bo, xrow, n)) {
+        return fail(PSGD_EALIAS, "%s: X_out partially overlaps X", name);
+    }
+    if (rows_overlap(G, bg, grow, X_out, bo, xrow, n)) return fail(PSGD_EALIAS, "%s: X_out overlaps G", name);
+    if (want_cd && (rows_overlap(cd_out, 8, 8, X_out, bo, xrow, n) || rows_overlap(cd_out, 8, 8, X, bx, xrow, n) ||
+                    rows_overlap(cd_out, 8, 8, G, bg, grow, n)))
+        return fail(PSGD_EALIAS, "%s: the distance output overlaps a data buffer", name);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    DeviceInfo* di = nullptr;
+    if (d == 0) {
+        if (!want_cd) return PSGD_OK;
+        if (int rc = device_info(&di, true)) return rc;
+        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, di->scratch, 0, cd_out);
+        const hipError_t e0 = hipGetLastError();
+        return e0 == hipSuccess ? PSGD_OK : hip_fail(e0, "consensus_final_kernel");
+    }
+    if (int rc = device_info(&di, want_cd)) return rc;
+    const bool vec4 = (d % 4 == 0) && (ldx % 4 == 0) && (ldo % 4 == 0) && (ldg % 4 == 0) && aligned_to(X, 16) &&
+                      aligned_to(X_out, 16) && aligned_to(G, 4 * sizeof(GT));
+    const int grid = persistent_grid(*di, vec4 ? d / 4 : d, kGridPerCu);
+    const dim3 g(grid), b(kThreads);
+    const Pitch ld{ldx, ldo, ldg};
+    const float neg_lr = -lr;
+    double* partials = want_cd ? di->scratch : nullptr;
+    if (vec4 && want_cd)
+        hipLaunchKernelGGL((mix_full_kernel<4, GT, true>), g, b, 0, s, X, X_out, G, n, d, ld, neg_lr, partials);
+    else if (vec4)
+        hipLaunchKernelGGL((mix_full_kernel<4, GT, false>), g, b, 0, s, X, X_out, G, n, d, ld, neg_lr, partials);
+    else if (want_cd)
+        hipLaunchKernelGGL((mix_full_kernel<1, GT, true>), g, b, 0, s, X, X_out, G, n, d, ld, neg_lr, partials);
+    else
+        hipLaunchKernelGGL((mix_full_kernel<1, GT, false>), g, b, 0, s, X, X_out, G, n, d, ld, neg_lr, partials);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, name);
+    if (want_cd) {
+        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, partials, grid, cd_out);
+        e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e, "consensus_final_kernel");
+    }
+    return PSGD_OK;
+}
+
 int consensus_enqueue(const float* X, int64_t ldx, int n, int64_t d, double* out_dev, hipStream_t s) {
     DeviceInfo* di = nullptr;
     if (int rc = device_info(&di, true)) return rc;
@@ -802,6 +938,19 @@ int psgd_mix_step_ex(const float* X, int64_t ldx, float* X_out, int64_t ldo, con
                                              stream);
     return psgd::mix_step_impl<float>("psgd_mix_step_ex", X, ldx, X_out, ldo, static_cast<const float*>(G), ldg, nbr,
                                       w, n, d, lr, delay_mode, cdist_out != nullptr, cdist_out, stream);
+}
+
+int psgd_mix_full(const float* X, int64_t ldx, float* X_out, int64_t ldo, const void* G, int64_t ldg, int g_is_bf16,
+                  int n, int64_t d, float lr, int delay_mode, double* cdist_out, void* stream) {
+    if (g_is_bf16 != 0 && g_is_bf16 != 1) {
+        psgd::clear_error();
+        return psgd::fail(PSGD_EINVAL, "psgd_mix_full: g_is_bf16=%d", g_is_bf16);
+    }
+    if (g_is_bf16)
+        return psgd::mix_full_impl<uint16_t>("psgd_mix_full", X, ldx, X_out, ldo, static_cast<const uint16_t*>(G), ldg,
+                                             n, d, lr, delay_mode, cdist_out, stream);
+    return psgd::mix_full_impl<float>("psgd_mix_full", X, ldx, X_out, ldo, static_cast<const float*>(G), ldg, n, d, lr,
+                                      delay_mode, cdist_out, stream);
 }
 
 double psgd_consensus_dist(const float* X, int n, int64_t d) {

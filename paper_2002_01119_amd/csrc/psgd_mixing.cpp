@@ -61,6 +61,8 @@ int psgd_build_mixing(int topology, int n, uint64_t seed, uint64_t step, int32_t
     if (!nbr || !w) return fail(PSGD_EINVAL, "psgd_build_mixing: null output pointer");
     if (n < 1 || n > PSGD_MAX_N)
         return fail(PSGD_EINVAL, "psgd_build_mixing: n=%d outside 1..%d", n, (int)PSGD_MAX_N);
+    if (topology == PSGD_TOPO_FULL)
+        return fail(PSGD_EINVAL, "psgd_build_mixing: the uniform topology has no 3-slot table, use psgd_mix_full");
     if (topology != PSGD_TOPO_RING && topology != PSGD_TOPO_RAND_RING)
         return fail(PSGD_EINVAL, "psgd_build_mixing: unknown topology %d", topology);
 

@@ -12,6 +12,7 @@ import numpy as np
 
 TOPO_RING = 0
 TOPO_RAND_RING = 1
+TOPO_FULL = 2
 DEG = 3
 MAX_N = 512
 
@@ -22,7 +23,7 @@ _lib = None
 
 EXPORTS = (
     "psgd_build_mixing", "psgd_mix_step", "psgd_mix_step_bf16g", "psgd_mix_step_cd",
-    "psgd_mix_step_cd_bf16g", "psgd_mix_step_ex", "psgd_consensus_dist", "psgd_consensus_dist_ex",
+    "psgd_mix_step_cd_bf16g", "psgd_mix_step_ex", "psgd_mix_full", "psgd_consensus_dist", "psgd_consensus_dist_ex",
     "psgd_consensus_dist_async", "psgd_synth_grad", "psgd_synth_grad_ex", "psgd_device_status", "psgd_last_error",
     "psgd_version",
 )
@@ -62,6 +63,9 @@ def load(reload=False):
     lib.psgd_mix_step_ex.restype = ctypes.c_int
     lib.psgd_mix_step_ex.argtypes = [vp, ctypes.c_int64, vp, ctypes.c_int64, vp, ctypes.c_int64, ctypes.c_int,
                                      vp, vp, ctypes.c_int, ctypes.c_int64, ctypes.c_float, ctypes.c_int, vp, vp]
+    lib.psgd_mix_full.restype = ctypes.c_int
+    lib.psgd_mix_full.argtypes = [vp, ctypes.c_int64, vp, ctypes.c_int64, vp, ctypes.c_int64, ctypes.c_int,
+                                  ctypes.c_int, ctypes.c_int64, ctypes.c_float, ctypes.c_int, vp, vp]
     lib.psgd_consensus_dist_ex.restype = ctypes.c_int
     lib.psgd_consensus_dist_ex.argtypes = [vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int64, vp, vp]
     lib.psgd_consensus_dist.restype = ctypes.c_double
@@ -168,6 +172,31 @@ def mix_step(X, X_out, G, nbr, w, lr, delay_mode=0, stream=None, cdist_out=None)
         fn = lib.psgd_mix_step_cd_bf16g if bf16 else lib.psgd_mix_step_cd
         _check(fn(X.data_ptr(), X_out.data_ptr(), G.data_ptr(), nbr.data_ptr(), w.data_ptr(), n, d,
                   float(lr), int(delay_mode), cd_ptr, sh))
+
+
+def mix_full(X, X_out, G, lr, delay_mode=0, stream=None, cdist_out=None):
+    """Enqueue X_out[i] = mean_j X[j] - lr * G[i] (global averaging, T_u).  Tensors as in mix_step."""
+    import torch
+    n, d, ldx = _rows_cols_pitch(X)
+    no, do, ldo = _rows_cols_pitch(X_out)
+    ng, dg, ldg = _rows_cols_pitch(G)
+    if (no, do) != (n, d) or (ng, dg) != (n, d):
+        raise ValueError("X, X_out and G must have one shape")
+    if X.dtype != torch.float32 or X_out.dtype != torch.float32:
+        raise ValueError("X and X_out must be float32")
+    if G.dtype == torch.float32:
+        bf16 = 0
+    elif G.dtype in (torch.bfloat16, torch.int16, torch.uint16):
+        bf16 = 1
+    else:
+        raise ValueError("G must be float32 or bfloat16 bit patterns")
+    cd_ptr = None
+    if cdist_out is not None:
+        if cdist_out.dtype != torch.float64 or cdist_out.numel() < 1 or cdist_out.device != X.device:
+            raise ValueError("cdist_out must be a float64 device tensor")
+        cd_ptr = cdist_out.data_ptr()
+    _check(load().psgd_mix_full(X.data_ptr(), ldx, X_out.data_ptr(), ldo, G.data_ptr(), ldg, bf16, n, d, float(lr),
+                                int(delay_mode), cd_ptr, _stream_handle(stream)))
 
 
 def consensus_dist(X):

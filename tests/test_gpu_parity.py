@@ -55,6 +55,20 @@ def run_step(psgd, X, G, nbr, w, lr, in_place=False, delay_mode=0):
     return out.cpu().numpy()
 
 
+def _pitched_views(n, d, pitch, g_bf16):
+    """X, X_out and G as interleaved row-pitched views of ONE pool: row i of X at i*pitch,
+    of X_out right behind it, of G behind that (pitch in fp32 elements)."""
+    pool = torch.zeros(n * pitch + 8, dtype=torch.float32, device="cuda:0")
+    X = pool.as_strided((n, d), (pitch, 1), 0)
+    Y = pool.as_strided((n, d), (pitch, 1), d)
+    if g_bf16:
+        gp = pool.view(torch.int16)
+        G = gp.as_strided((n, d), (2 * pitch, 1), 4 * d)
+    else:
+        G = pool.as_strided((n, d), (pitch, 1), 2 * d)
+    return pool, X, Y, G
+
+
 SHAPES = [(1, 1), (1, 1000), (2, 5), (3, 4), (4, 7), (5, 1024), (8, 4100), (8, 70001),
           (16, 3 * 1024 * 4 + 4), (33, 2052), (64, 9 * 1024 + 8), (128, 4096 + 12), (512, 260)]
 
@@ -321,21 +335,53 @@ def test_fused_distance_special_cases(psgd):
     assert rc == 0 and cz.item() == 0.0
 
 
+# ------------------------------------------------------------------------- global averaging (T_u)
+@pytest.mark.parametrize("n,d", SHAPES)
+@pytest.mark.parametrize("gkind", ["f32", "bf16"])
+def test_mix_full_matches_oracle(psgd, n, d, gkind):
+    """S-PSGD's / D1D-PSGD's T_u: every learner gets the mean model, then its own gradient."""
+    X = inp.host_normal_f32((n, d), 1.0, 1300 + n) + np.float32(2.0)
+    G = inp.host_normal_f32((n, d), 0.5, 1400 + n)
+    if gkind == "bf16":
+        G = inp.f32_to_bf16_bits(G)
+    want = orc.mix_step(X, G, orc.uniform_matrix(n), 0.1)
+    Xd = dev(X)
+    Gd = bits_dev(G) if gkind == "bf16" else dev(G)
+    out = torch.full_like(Xd, float("nan"))
+    c = torch.zeros(1, dtype=torch.float64, device="cuda:0")
+    psgd.mix_full(Xd, out, Gd, 0.1, cdist_out=c)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert_close(got, want)
+    c_ref = orc.consensus_dist(got)
+    assert abs(c.item() - c_ref) <= REL * c_ref + 1e-300
+    out2 = torch.full_like(Xd, float("nan"))
+    psgd.mix_full(Xd, out2, Gd, 0.1, delay_mode=1)          # no distance, delay flag
+    psgd.mix_full(Xd, Xd, Gd, 0.1)                          # in place
+    torch.cuda.synchronize()
+    assert np.array_equal(out2.cpu().numpy().view(np.uint32), got.view(np.uint32))
+    assert np.array_equal(Xd.cpu().numpy().view(np.uint32), got.view(np.uint32))
+    with pytest.raises(psgd.PsgdError):
+        psgd.mix_full(Xd, Xd, Gd, 0.1, delay_mode=1)
+
+
+def test_mix_full_pitched_and_consensus_after_averaging(psgd):
+    n, d, pitch = 16, 2052, 7000
+    Xh = inp.host_normal_f32((n, d), 1.0, 5)
+    pool, X, Y, G = _pitched_views(n, d, pitch, False)
+    X.copy_(dev(Xh))
+    psgd.mix_full(X, Y, G, 0.5)            # G = 0: every replica becomes the mean
+    torch.cuda.synchronize()
+    got = Y.cpu().numpy()
+    assert_close(got, orc.mix_step(Xh, np.zeros_like(Xh), orc.uniform_matrix(n), 0.5))
+    assert np.array_equal(got, np.broadcast_to(got[0], got.shape))       # exact consensus
+    c = torch.ones(1, dtype=torch.float64, device="cuda:0")
+    psgd.consensus_dist_async(Y, c)
+    torch.cuda.synchronize()
+    assert c.item() == 0.0
+
+
 # ------------------------------------------------------------------------- pitched rows
-def _pitched_views(n, d, pitch, g_bf16):
-    """X, X_out and G as interleaved row-pitched views of ONE pool: row i of X at i*pitch,
-    of X_out right behind it, of G behind that (pitch in fp32 elements)."""
-    pool = torch.zeros(n * pitch + 8, dtype=torch.float32, device="cuda:0")
-    X = pool.as_strided((n, d), (pitch, 1), 0)
-    Y = pool.as_strided((n, d), (pitch, 1), d)
-    if g_bf16:
-        gp = pool.view(torch.int16)
-        G = gp.as_strided((n, d), (2 * pitch, 1), 4 * d)
-    else:
-        G = pool.as_strided((n, d), (pitch, 1), 2 * d)
-    return pool, X, Y, G
-
-
 @pytest.mark.parametrize("n,d,pitch", [(2, 8, 32), (8, 4100, 3 * 4100 + 4), (16, 1001, 3100), (64, 2052, 7000),
                                        (128, 516, 2048), (5, 1, 3)])
 @pytest.mark.parametrize("gkind", ["f32", "bf16"])

@@ -129,8 +129,11 @@ def run_workload(psgd, wl, topo, steps=None, layout="dense"):
     c_out = torch.zeros(steps, dtype=torch.float64, device="cuda:0")
     c_chk = torch.zeros(1, dtype=torch.float64, device="cuda:0")
     for k in range(steps):
-        nbr, w = psgd.build_mixing(topo, n, wl.seed_perm, k)
-        T = orc.densify(nbr, w)
+        if topo == orc.TOPO_FULL:
+            T = orc.uniform_matrix(n)
+        else:
+            nbr, w = psgd.build_mixing(topo, n, wl.seed_perm, k)
+            T = orc.densify(nbr, w)
         Ts.append(T)
         if wl.delay:
             noise.normal_(0.0, wl.sigma_g, generator=gen)
@@ -145,7 +148,9 @@ def run_workload(psgd, wl, topo, steps=None, layout="dense"):
                 Gbuf.copy_(G)
                 G = Gbuf
             Go = pull(G, cols_t)
-        if k % 2 == 0:      # alternate the fused entry point with the two separate calls
+        if topo == orc.TOPO_FULL:
+            psgd.mix_full(X, Y, G, wl.lr, delay_mode=1 if wl.delay else 0, cdist_out=c_out[k:k + 1])
+        elif k % 2 == 0:      # alternate the fused entry point with the two separate calls
             psgd.mix_step(X, Y, G, dev(nbr), dev(w), wl.lr, delay_mode=1 if wl.delay else 0,
                           cdist_out=c_out[k:k + 1])
             if k < 4:
@@ -229,6 +234,20 @@ def test_cfg4_delay_by_one(psgd):
     cdist, Ts, _ = run_workload(psgd, wl, orc.TOPO_RAND_RING, layout="pitched")
     expect = expected_consensus_d1d(Ts, wl.d, wl.sigma_x, wl.sigma_g, wl.lr, wl.grad_pull)
     check_against_expectation(cdist, expect, wl.d, wl.n, "cfg4")
+    torch.cuda.empty_cache()
+
+
+def test_cfg4_shape_with_global_averaging(psgd):
+    """The paper's own D1D-PSGD: T_u (allreduce / L, Sec. 4, Eq. 13) with the gradient taken one
+    iterate earlier (Eq. 14), on workload 4's shape and inputs, 30 steps."""
+    wl = inp.workload(4)
+    cdist, Ts, X = run_workload(psgd, wl, orc.TOPO_FULL, steps=30, layout="pitched")
+    expect = expected_consensus_d1d(Ts, wl.d, wl.sigma_x, wl.sigma_g, wl.lr, wl.grad_pull)
+    check_against_expectation(cdist, expect, wl.d, wl.n, "cfg4 T_u")
+    # spectral gap 1: after one averaging the distance is only what the last gradients put back
+    floor = wl.d * (wl.n - 1) * (wl.lr * wl.sigma_g) ** 2
+    assert abs(cdist[-1] / floor - 1) < 0.05
+    del X
     torch.cuda.empty_cache()
 
 

@@ -19,7 +19,7 @@ def test_library_exports_every_declared_symbol():
     with open(os.path.join(ROOT, "include", "psgd.h")) as f:
         text = re.sub(r"/\*.*?\*/", "", f.read(), flags=re.S)
     declared = sorted(set(re.findall(r"\b(psgd_[a-z0-9_]+)\s*\(", text)))
-    assert len(declared) >= 14
+    assert len(declared) >= 15
     for name in declared:
         assert hasattr(lib, name), name
     assert sorted(psgd.EXPORTS) == declared
@@ -67,6 +67,8 @@ def test_build_mixing_rejects_bad_arguments():
     assert lib.psgd_build_mixing(0, psgd.MAX_N + 1, 0, 0, nbr, w) == psgd.EINVAL
     assert lib.psgd_build_mixing(7, 4, 0, 0, nbr, w) == psgd.EINVAL
     assert "topology" in psgd.last_error()
+    assert lib.psgd_build_mixing(psgd.TOPO_FULL, 4, 0, 0, nbr, w) == psgd.EINVAL
+    assert "psgd_mix_full" in psgd.last_error()
     assert lib.psgd_build_mixing(0, 4, 0, 0, None, w) == psgd.EINVAL
     assert lib.psgd_build_mixing(0, 4, 0, 0, nbr, None) == psgd.EINVAL
     assert lib.psgd_build_mixing(0, 4, 0, 0, nbr, w) == psgd.OK
@@ -104,6 +106,14 @@ def test_mix_step_argument_checks_need_no_device():
     assert lib.psgd_mix_step_cd(A, B, C, T1, T2, n, d, 0.1, 0, 0x3000004, None) == psgd.EALIGN
     assert lib.psgd_mix_step_cd(A, B, C, T1, T2, n, d, 0.1, 0, B + 8, None) == psgd.EALIAS
     assert lib.psgd_mix_step_cd_bf16g(A, A, C, T1, T2, n, d, 0.1, 1, 0x3000000, None) == psgd.EALIAS
+    full = lib.psgd_mix_full
+    assert full(A, d, B, d, C, d, 0, n, d, 0.1, 0, None, None) in (psgd.OK, psgd.EHIP)
+    assert full(None, d, B, d, C, d, 0, n, d, 0.1, 0, None, None) == psgd.EINVAL
+    assert full(A, d, A, d, C, d, 0, n, d, 0.1, 1, None, None) == psgd.EALIAS
+    assert full(A, d, A + 8, d, C, d, 0, n, d, 0.1, 0, None, None) == psgd.EALIAS
+    assert full(A, d, B, d, C, d, 3, n, d, 0.1, 0, None, None) == psgd.EINVAL
+    assert full(A, d - 1, B, d, C, d, 0, n, d, 0.1, 0, None, None) == psgd.EINVAL
+    assert full(A, d, A, d, C, d, 0, n, 0, 0.1, 0, None, None) == psgd.OK
     ex = lib.psgd_mix_step_ex
     # pitched rows: arrays may interleave (X rows at A + i*P, X_out rows right behind them) ...
     P = 3 * d            # elements
