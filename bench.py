@@ -84,6 +84,9 @@ def main():
     ap.add_argument("--unfused", action="store_true",
                     help="separate mix and consensus kernels instead of the fused psgd_mix_step_cd")
     ap.add_argument("--in-place", action="store_true", help="mix in place instead of ping-pong buffers")
+    ap.add_argument("--overlap", action="store_true",
+                    help="delay-by-one workloads: run the gradient producer of step k+1 on a second stream, "
+                         "concurrently with the mix of step k (Sec. 4: gradient computation beside the averaging)")
     ap.add_argument("--global-average", action="store_true",
                     help="mix with T_u = (1/n) 1 1^T (psgd_mix_full: S-PSGD / the paper's own D1D-PSGD) instead of "
                          "the workload's ring table")
@@ -194,6 +197,11 @@ def main():
     ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(total)]
     ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(total)]
     ev2 = [torch.cuda.Event(enable_timing=True) for _ in range(total)]
+    stream2 = torch.cuda.Stream(device=dev)
+    ev_prod = [torch.cuda.Event() for _ in range(total + 1)]
+    if wl.delay and args.overlap:
+        psgd.synth_grad(X_prev, noise, Gs[0], wl.grad_pull, stream=stream2)      # G_0 from X_{-1} = X_0
+        ev_prod[0].record(stream2)
     torch.cuda.synchronize()
 
     def one_step(k):
@@ -204,7 +212,10 @@ def main():
         nbr_dev[k].copy_(nbr_host[k], non_blocking=True)
         w_dev[k].copy_(w_host[k], non_blocking=True)
         G = Gs[k % 2]
-        if wl.delay:
+        overlap = wl.delay and args.overlap
+        if overlap:
+            stream.wait_event(ev_prod[k])                    # G_k was produced on the second stream
+        elif wl.delay:
             psgd.synth_grad(X_prev, noise, G, wl.grad_pull, stream=stream)
         fused = not (args.unfused or args.no_consensus)
         ev0[k].record(stream)
@@ -218,6 +229,13 @@ def main():
         if not (fused or args.no_consensus):
             psgd.consensus_dist_async(Y, cdist[k:k + 1], stream=stream)
         ev2[k].record(stream)
+        if overlap and k + 1 < total:
+            # producer of G_{k+1} = c * X_k + noise: needs X_k (complete since step k-1) and the gradient
+            # buffer that step k-1 read; runs beside the mix of step k, which only reads X_k
+            if k > 0:
+                stream2.wait_event(ev2[k - 1])
+            psgd.synth_grad(X, noise, Gs[(k + 1) % 2], wl.grad_pull, stream=stream2)
+            ev_prod[k + 1].record(stream2)
         if wl.delay:
             X_prev, X, Y = X, Y, X_prev
         elif not args.in_place:
@@ -293,7 +311,7 @@ def main():
             "lr": wl.lr,
             "delay_by_one": wl.delay, "consensus_every_step": not args.no_consensus,
             "consensus_fused_into_mix_kernel": fused,
-            "in_place": bool(args.in_place),
+            "in_place": bool(args.in_place), "producer_overlapped": bool(wl.delay and args.overlap),
             "hbm_layout": layout_report,
         },
         "roofline": {
