@@ -42,6 +42,7 @@ enum {
 
 enum { PSGD_DEG = 3 };       /* slots per table row: self, left, right */
 enum { PSGD_MAX_N = 512 };   /* largest learner count the kernels stage in LDS */
+enum { PSGD_MAX_DEG = 32, PSGD_MAX_TABLE = 4096 };  /* psgd_mix_step_deg: slots per row, n * deg */
 
 typedef enum {
     PSGD_OK = 0,
@@ -155,6 +156,23 @@ int psgd_mix_step_ex(const float* X, int64_t ldx, float* X_out, int64_t ldo,
                      const void* G, int64_t ldg, int g_is_bf16,
                      const int32_t* nbr, const float* w,
                      int n, int64_t d, float lr, int delay_mode, double* cdist_out, void* stream);
+
+/*
+ * psgd_mix_step_deg - the step of Sec. 2, Eq. 2 for any sparse mixing matrix given as a table
+ * with `deg` slots per row: X_out[i,:] = sum_{s<deg} w[i*deg+s] * X[nbr[i*deg+s],:] - lr*G[i,:]
+ * (nbr, w: device, [n * deg]).  Covers what the 3-slot ring tables cannot: more neighbours per
+ * learner, lazy walks, or the product of several mixing rounds collapsed into one matrix (the
+ * remedy of the prior work the paper cites in Sec. 6).  1 <= deg <= PSGD_MAX_DEG and
+ * n * deg <= PSGD_MAX_TABLE.  Per element: acc = w0 * x0; acc = fma(w_s, x_s, acc) for
+ * s = 1..deg-1 in table order; out = fma(-lr, g, acc).  deg = 3 is psgd_mix_step_ex (ring
+ * tables then take the register walk); other degrees always stage an [n x columns] tile in
+ * LDS.  Everything else (pitches, gradient type, in-place rule, cdist_out, errors) is as in
+ * psgd_mix_step_ex.
+ */
+int psgd_mix_step_deg(const float* X, int64_t ldx, float* X_out, int64_t ldo,
+                      const void* G, int64_t ldg, int g_is_bf16,
+                      const int32_t* nbr, const float* w, int deg,
+                      int n, int64_t d, float lr, int delay_mode, double* cdist_out, void* stream);
 
 /*
  * psgd_mix_full - the step with global averaging, T = T_u = (1/L) 1 1^T:

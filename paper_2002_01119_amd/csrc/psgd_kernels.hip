@@ -104,16 +104,16 @@ struct Lds {
     float* w;
     char* scratch;
 };
-__host__ __device__ inline size_t lds_table_bytes(int n) {
-    return (size_t)n * sizeof(RingEnt) + (size_t)n * 3 * (sizeof(int) + sizeof(float));
+__host__ __device__ inline size_t lds_table_bytes(int n, int deg = 3) {
+    return (size_t)n * sizeof(RingEnt) + (size_t)n * deg * (sizeof(int) + sizeof(float));
 }
-__device__ __forceinline__ Lds carve(char* base, int n) {
+__device__ __forceinline__ Lds carve(char* base, int n, int deg = 3) {
     Lds l;
     l.ring = reinterpret_cast<RingEnt*>(base);
     l.nbr = reinterpret_cast<int*>(base + (size_t)n * sizeof(RingEnt));
-    l.w = reinterpret_cast<float*>(l.nbr + 3 * n);
-    // n * 40 bytes of tables; keep the scratch 16-byte aligned
-    l.scratch = base + ((lds_table_bytes(n) + 15) & ~(size_t)15);
+    l.w = reinterpret_cast<float*>(l.nbr + deg * n);
+    // keep the scratch 16-byte aligned
+    l.scratch = base + ((lds_table_bytes(n, deg) + 15) & ~(size_t)15);
     return l;
 }
 
@@ -340,9 +340,19 @@ __host__ __device__ inline size_t tile_cd_bytes(int lpr, int vec) {
     return (size_t)lpr * vec * sizeof(float) + 8 + (size_t)kThreads * 2 * vec * sizeof(double);
 }
 
+// One output group from the tile: slots in table order, acc = w0 * x0, then one fma per
+// further slot, then the gradient term (for 3 slots this is exactly mix_one's order).
+template <typename V>
+__device__ __forceinline__ V mix_slots(const V* tile, const int* nbr, const float* w, int deg, int lpr, int lane, V g,
+                                       float neg_lr) {
+    V acc = tile[nbr[0] * lpr + lane] * w[0];
+    for (int s = 1; s < deg; ++s) acc = vfma(w[s], tile[nbr[s] * lpr + lane], acc);
+    return vfma(neg_lr, g, acc);
+}
+
 template <int VEC, typename GT, bool CD>
 __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ G, const Lds& l,
-                            int n, Pitch ld, int64_t ncg, float neg_lr, int lpr, double inv_n) {
+                            int n, Pitch ld, int64_t ncg, float neg_lr, int lpr, double inv_n, int deg = 3) {
     typedef typename Cols<VEC>::T V;
     const Cols<VEC> tag{};
     V* tile = reinterpret_cast<V*>(l.scratch);
@@ -360,11 +370,8 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
         __syncthreads();
         if (active)
             for (int r = rg; r < n; r += nrg) {
-                const V self = tile[l.nbr[3 * r] * lpr + lane];
-                const V left = tile[l.nbr[3 * r + 1] * lpr + lane];
-                const V right = tile[l.nbr[3 * r + 2] * lpr + lane];
                 const V g = ld_g(G + (int64_t)r * ld.g + col, tag);
-                const V out = mix_one<V>(l.w[3 * r], l.w[3 * r + 1], l.w[3 * r + 2], self, left, right, g, neg_lr);
+                const V out = mix_slots<V>(tile, l.nbr + deg * r, l.w + deg * r, deg, lpr, lane, g, neg_lr);
                 st_x(Xout + (int64_t)r * ld.o + col, out);
                 if (CD && r == 0) pivot[lane] = out;
             }
@@ -380,11 +387,8 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
                 pivot_of(pivot[lane], s);
                 for (int r = rg; r < n; r += nrg) {
                     if (r == 0) continue;
-                    const V self = tile[l.nbr[3 * r] * lpr + lane];
-                    const V left = tile[l.nbr[3 * r + 1] * lpr + lane];
-                    const V right = tile[l.nbr[3 * r + 2] * lpr + lane];
                     const V g = ld_g(G + (int64_t)r * ld.g + col, tag);
-                    acc_diff<VEC>(a, b, mix_one<V>(l.w[3 * r], l.w[3 * r + 1], l.w[3 * r + 2], self, left, right, g, neg_lr), s);
+                    acc_diff<VEC>(a, b, mix_slots<V>(tile, l.nbr + deg * r, l.w + deg * r, deg, lpr, lane, g, neg_lr), s);
                 }
             }
 #pragma unroll
@@ -442,6 +446,36 @@ __global__ __launch_bounds__(kThreads) void mix_step_kernel(const float* X, floa
     } else {
         total = tile_path<VEC, GT, CD>(X, Xout, G, l, n, ld, ncg, neg_lr, lpr, inv_n);
     }
+    if (CD) {
+        const double bs = block_sum(total, lds4);
+        if (threadIdx.x == 0) partials[blockIdx.x] = bs;
+    }
+}
+
+// Any table with `deg` slots per row (sparse doubly stochastic matrices beyond the ring:
+// more neighbours, lazy walks, products of several mixing rounds).  Always the tiled path.
+template <int VEC, typename GT, bool CD>
+__global__ __launch_bounds__(kThreads) void mix_deg_kernel(const float* X, float* Xout, const GT* __restrict__ G,
+                                                           const int32_t* __restrict__ nbr,
+                                                           const float* __restrict__ w, int deg, int n, int64_t d,
+                                                           Pitch ld, float neg_lr, int lpr,
+                                                           double* __restrict__ partials) {
+    extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+    __shared__ double lds4[4];
+    const Lds l = carve(lds_raw, n, deg);
+    int ok = 1;
+    for (int e = threadIdx.x; e < deg * n; e += kThreads) {
+        const int v = nbr[e];
+        l.nbr[e] = v;
+        l.w[e] = w[e];
+        ok &= (unsigned)v < (unsigned)n;
+    }
+    if (!__syncthreads_and(ok)) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&g_status_word, 1);
+        if (CD && threadIdx.x == 0) partials[blockIdx.x] = __builtin_nan("");
+        return;
+    }
+    const double total = tile_path<VEC, GT, CD>(X, Xout, G, l, n, ld, d / VEC, neg_lr, lpr, 1.0 / (double)n, deg);
     if (CD) {
         const double bs = block_sum(total, lds4);
         if (threadIdx.x == 0) partials[blockIdx.x] = bs;
@@ -714,10 +748,13 @@ int launch_mix(const DeviceInfo& di, size_t lds_bytes, hipStream_t s, const floa
 template <typename GT>
 int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, int64_t ldo, const GT* G, int64_t ldg,
                   const int32_t* nbr, const float* w, int n, int64_t d, float lr, int delay_mode, bool want_cd,
-                  double* cd_out, void* stream) {
+                  double* cd_out, void* stream, int deg = 3) {
     clear_error();
     if (!X || !X_out || !G || !nbr || !w || (want_cd && !cd_out)) return fail(PSGD_EINVAL, "%s: null pointer", name);
     if (n < 1 || n > PSGD_MAX_N) return fail(PSGD_EINVAL, "%s: n=%d outside 1..%d", name, n, (int)PSGD_MAX_N);
+    if (deg < 1 || deg > PSGD_MAX_DEG || (int64_t)n * deg > PSGD_MAX_TABLE)
+        return fail(PSGD_EINVAL, "%s: deg=%d outside 1..%d or n*deg > %d", name, deg, (int)PSGD_MAX_DEG,
+                    (int)PSGD_MAX_TABLE);
     if (d < 0) return fail(PSGD_EINVAL, "%s: d=%lld is negative", name, (long long)d);
     if (delay_mode != 0 && delay_mode != 1) return fail(PSGD_EINVAL, "%s: delay_mode=%d", name, delay_mode);
     if (n > 1 && (ldx < d || ldo < d || ldg < d))
@@ -755,20 +792,44 @@ int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
     const bool vec4 = (d % 4 == 0) && (ldx % 4 == 0) && (ldo % 4 == 0) && (ldg % 4 == 0) && aligned_to(X, 16) &&
                       aligned_to(X_out, 16) && aligned_to(G, 4 * sizeof(GT));
     const int vec = vec4 ? 4 : 1;
-    // Tile shape of the fallback path: widest power-of-two lane count whose tile fits.
+    // Tile shape of the tiled path: widest power-of-two lane count whose tile (plus the
+    // combine arrays of the fused distance) fits the budget and the 64 KB a workgroup may use.
+    const size_t lds_limit = 64 * 1024 - 64;
+    const size_t table_bytes = (lds_table_bytes(n, deg) + 15) & ~(size_t)15;
     const size_t tile_budget = want_cd ? (size_t)kTileBytes / 2 : (size_t)kTileBytes;
     int lpr = 64;
-    while (lpr > 1 && (size_t)n * lpr * vec * sizeof(float) > tile_budget) lpr >>= 1;
-    size_t scratch_bytes = (size_t)n * lpr * vec * sizeof(float) + (want_cd ? tile_cd_bytes(lpr, vec) : 0);
+    size_t scratch_bytes = 0;
+    for (;; lpr >>= 1) {
+        const size_t tile = (size_t)n * lpr * vec * sizeof(float);
+        scratch_bytes = tile + (want_cd ? tile_cd_bytes(lpr, vec) : 0);
+        if ((tile <= tile_budget && table_bytes + scratch_bytes <= lds_limit) || lpr == 1) break;
+    }
     if (scratch_bytes < (size_t)n * 4 * sizeof(int)) scratch_bytes = (size_t)n * 4 * sizeof(int);
-    const size_t lds_bytes = ((lds_table_bytes(n) + 15) & ~(size_t)15) + scratch_bytes;
-    if (lds_bytes > 64 * 1024 - 64) return fail(PSGD_EINVAL, "%s: n=%d needs %zu bytes of LDS", name, n, lds_bytes);
+    const size_t lds_bytes = table_bytes + scratch_bytes;
+    if (lds_bytes > lds_limit) return fail(PSGD_EINVAL, "%s: n=%d, deg=%d needs %zu bytes of LDS", name, n, deg, lds_bytes);
 
     const float neg_lr = -lr;
     const Pitch ld{ldx, ldo, ldg};
     double* partials = want_cd ? di->scratch : nullptr;
     int grid = 0;
-    if (vec4 && want_cd)
+    if (deg != 3) {
+        const int64_t ntiles = (d / vec + lpr - 1) / lpr;
+        const int64_t cap = (int64_t)di->cus * 2;
+        grid = (int)(ntiles < cap ? ntiles : cap);
+        const dim3 g(grid), b(kThreads);
+        if (vec4 && want_cd)
+            hipLaunchKernelGGL((mix_deg_kernel<4, GT, true>), g, b, lds_bytes, s, X, X_out, G, nbr, w, deg, n, d, ld,
+                               neg_lr, lpr, partials);
+        else if (vec4)
+            hipLaunchKernelGGL((mix_deg_kernel<4, GT, false>), g, b, lds_bytes, s, X, X_out, G, nbr, w, deg, n, d, ld,
+                               neg_lr, lpr, partials);
+        else if (want_cd)
+            hipLaunchKernelGGL((mix_deg_kernel<1, GT, true>), g, b, lds_bytes, s, X, X_out, G, nbr, w, deg, n, d, ld,
+                               neg_lr, lpr, partials);
+        else
+            hipLaunchKernelGGL((mix_deg_kernel<1, GT, false>), g, b, lds_bytes, s, X, X_out, G, nbr, w, deg, n, d, ld,
+                               neg_lr, lpr, partials);
+    } else if (vec4 && want_cd)
         grid = launch_mix<4, GT, true>(*di, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials);
     else if (vec4)
         grid = launch_mix<4, GT, false>(*di, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials);
@@ -938,6 +999,21 @@ int psgd_mix_step_ex(const float* X, int64_t ldx, float* X_out, int64_t ldo, con
                                              stream);
     return psgd::mix_step_impl<float>("psgd_mix_step_ex", X, ldx, X_out, ldo, static_cast<const float*>(G), ldg, nbr,
                                       w, n, d, lr, delay_mode, cdist_out != nullptr, cdist_out, stream);
+}
+
+int psgd_mix_step_deg(const float* X, int64_t ldx, float* X_out, int64_t ldo, const void* G, int64_t ldg, int g_is_bf16,
+                      const int32_t* nbr, const float* w, int deg, int n, int64_t d, float lr, int delay_mode,
+                      double* cdist_out, void* stream) {
+    if (g_is_bf16 != 0 && g_is_bf16 != 1) {
+        psgd::clear_error();
+        return psgd::fail(PSGD_EINVAL, "psgd_mix_step_deg: g_is_bf16=%d", g_is_bf16);
+    }
+    if (g_is_bf16)
+        return psgd::mix_step_impl<uint16_t>("psgd_mix_step_deg", X, ldx, X_out, ldo, static_cast<const uint16_t*>(G),
+                                             ldg, nbr, w, n, d, lr, delay_mode, cdist_out != nullptr, cdist_out,
+                                             stream, deg);
+    return psgd::mix_step_impl<float>("psgd_mix_step_deg", X, ldx, X_out, ldo, static_cast<const float*>(G), ldg, nbr,
+                                      w, n, d, lr, delay_mode, cdist_out != nullptr, cdist_out, stream, deg);
 }
 
 int psgd_mix_full(const float* X, int64_t ldx, float* X_out, int64_t ldo, const void* G, int64_t ldg, int g_is_bf16,

@@ -23,7 +23,7 @@ _lib = None
 
 EXPORTS = (
     "psgd_build_mixing", "psgd_mix_step", "psgd_mix_step_bf16g", "psgd_mix_step_cd",
-    "psgd_mix_step_cd_bf16g", "psgd_mix_step_ex", "psgd_mix_full", "psgd_consensus_dist", "psgd_consensus_dist_ex",
+    "psgd_mix_step_cd_bf16g", "psgd_mix_step_ex", "psgd_mix_step_deg", "psgd_mix_full", "psgd_consensus_dist", "psgd_consensus_dist_ex",
     "psgd_consensus_dist_async", "psgd_synth_grad", "psgd_synth_grad_ex", "psgd_device_status", "psgd_last_error",
     "psgd_version",
 )
@@ -63,6 +63,10 @@ def load(reload=False):
     lib.psgd_mix_step_ex.restype = ctypes.c_int
     lib.psgd_mix_step_ex.argtypes = [vp, ctypes.c_int64, vp, ctypes.c_int64, vp, ctypes.c_int64, ctypes.c_int,
                                      vp, vp, ctypes.c_int, ctypes.c_int64, ctypes.c_float, ctypes.c_int, vp, vp]
+    lib.psgd_mix_step_deg.restype = ctypes.c_int
+    lib.psgd_mix_step_deg.argtypes = [vp, ctypes.c_int64, vp, ctypes.c_int64, vp, ctypes.c_int64, ctypes.c_int,
+                                      vp, vp, ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_float,
+                                      ctypes.c_int, vp, vp]
     lib.psgd_mix_full.restype = ctypes.c_int
     lib.psgd_mix_full.argtypes = [vp, ctypes.c_int64, vp, ctypes.c_int64, vp, ctypes.c_int64, ctypes.c_int,
                                   ctypes.c_int, ctypes.c_int64, ctypes.c_float, ctypes.c_int, vp, vp]
@@ -130,7 +134,8 @@ def build_mixing(topology, n, seed=0, step=0):
 
 def mix_step(X, X_out, G, nbr, w, lr, delay_mode=0, stream=None, cdist_out=None):
     """Enqueue X_out = mix(X) - lr * G.  All arguments are device tensors; G is float32, or
-    bfloat16 / int16 / uint16 (bf16 bit patterns).  X, X_out and G are [n, d] with unit
+    bfloat16 / int16 / uint16 (bf16 bit patterns).  nbr / w are [n, deg] tables (deg = 3 for
+    the ring tables of build_mixing; any other deg selects psgd_mix_step_deg).  X, X_out and G are [n, d] with unit
     stride along d; their rows may be pitched (stride(0) >= d), which selects
     psgd_mix_step_ex.  With cdist_out (device float64 tensor, >= 1 element) the fused
     variant also writes the consensus distance of X_out there."""
@@ -142,9 +147,10 @@ def mix_step(X, X_out, G, nbr, w, lr, delay_mode=0, stream=None, cdist_out=None)
         raise ValueError("X, X_out and G must have one shape")
     if X.dtype != torch.float32 or X_out.dtype != torch.float32:
         raise ValueError("X and X_out must be float32")
-    if nbr.dtype != torch.int32 or w.dtype != torch.float32 or nbr.numel() != n * DEG \
-            or w.numel() != n * DEG or not nbr.is_contiguous() or not w.is_contiguous():
-        raise ValueError("nbr must be int32 [n,3] and w float32 [n,3], contiguous")
+    if nbr.dtype != torch.int32 or w.dtype != torch.float32 or nbr.numel() % n or nbr.numel() != w.numel() \
+            or not nbr.is_contiguous() or not w.is_contiguous():
+        raise ValueError("nbr must be int32 [n,deg] and w float32 [n,deg], contiguous")
+    deg = nbr.numel() // n
     for t in (X_out, G, nbr, w):
         if t.device != X.device:
             raise ValueError("all tensors must live on one device")
@@ -161,7 +167,10 @@ def mix_step(X, X_out, G, nbr, w, lr, delay_mode=0, stream=None, cdist_out=None)
             raise ValueError("cdist_out must be a float64 device tensor")
         cd_ptr = cdist_out.data_ptr()
     sh = _stream_handle(stream)
-    if (ldx, ldo, ldg) != (d, d, d):
+    if deg != DEG:
+        _check(lib.psgd_mix_step_deg(X.data_ptr(), ldx, X_out.data_ptr(), ldo, G.data_ptr(), ldg, int(bf16),
+                                     nbr.data_ptr(), w.data_ptr(), deg, n, d, float(lr), int(delay_mode), cd_ptr, sh))
+    elif (ldx, ldo, ldg) != (d, d, d):
         _check(lib.psgd_mix_step_ex(X.data_ptr(), ldx, X_out.data_ptr(), ldo, G.data_ptr(), ldg, int(bf16),
                                     nbr.data_ptr(), w.data_ptr(), n, d, float(lr), int(delay_mode), cd_ptr, sh))
     elif cd_ptr is None:

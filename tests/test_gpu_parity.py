@@ -335,6 +335,110 @@ def test_fused_distance_special_cases(psgd):
     assert rc == 0 and cz.item() == 0.0
 
 
+# ------------------------------------------------------------------------- degree-K tables
+def _perm_sum_table(n, deg, rng):
+    """Doubly stochastic table with `deg` slots: a convex combination of deg permutations."""
+    c = rng.random(deg).astype(np.float32) + np.float32(0.1)
+    c /= c.sum()
+    nbr = np.stack([rng.permutation(n) for _ in range(deg)], axis=1).astype(np.int32)
+    w = np.tile(c.astype(np.float32), (n, 1))
+    return nbr, w
+
+
+@pytest.mark.parametrize("n,d,deg", [(4, 9, 1), (6, 2048, 2), (16, 4 * 3000, 5), (64, 1025, 8), (128, 8192 + 4, 4),
+                                     (128, 516, 32), (300, 516, 13), (8, 70001, 7)])
+@pytest.mark.parametrize("gkind", ["f32", "bf16"])
+def test_degree_k_tables(psgd, n, d, deg, gkind):
+    rng = np.random.default_rng(n * 13 + deg)
+    nbr, w = _perm_sum_table(n, deg, rng)
+    T = orc.densify(nbr, w)
+    assert np.allclose(T.sum(0), 1, atol=1e-5) and np.allclose(T.sum(1), 1, atol=1e-5)
+    X = inp.host_normal_f32((n, d), 1.0, 1500 + n)
+    G = inp.host_normal_f32((n, d), 0.5, 1600 + n)
+    if gkind == "bf16":
+        G = inp.f32_to_bf16_bits(G)
+    want = orc.mix_step(X, G, T, 0.2)
+    got, c = run_step_cd(psgd, X, G, nbr, w, 0.2)
+    assert_close(got, want, rel=REL * max(1.0, deg / 4))      # deg + 1 roundings instead of 4
+    c_ref = orc.consensus_dist(got)
+    assert abs(c - c_ref) <= REL * c_ref
+    got_ip, c_ip = run_step_cd(psgd, X, G, nbr, w, 0.2, in_place=True)
+    assert np.array_equal(got_ip.view(np.uint32), got.view(np.uint32)) and c_ip == c
+    assert np.array_equal(run_step(psgd, X, G, nbr, w, 0.2).view(np.uint32), got.view(np.uint32))
+
+
+def test_two_ring_hops_as_one_degree5_table(psgd):
+    """A ring that also averages with the second neighbours (5-point stencil, weights 1/5)."""
+    n, d = 16, 3000
+    nbr = np.stack([(np.arange(n) + k) % n for k in (0, -1, 1, -2, 2)], axis=1).astype(np.int32)
+    w = np.full((n, 5), 0.2, np.float32)
+    T = orc.densify(nbr, w)
+    lam = orc.spectrum(T)
+    want_lam = np.sort([(1 + 2 * np.cos(2 * np.pi * k / n) + 2 * np.cos(4 * np.pi * k / n)) / 5 for k in range(n)])[::-1]
+    assert np.allclose(lam, want_lam, atol=1e-6)          # circulant: Fourier transform of the first row
+    X = inp.host_normal_f32((n, d), 1.0, 3)
+    G = inp.host_normal_f32((n, d), 1.0, 4)
+    assert_close(run_step(psgd, X, G, nbr, w, 0.1), orc.mix_step(X, G, T, 0.1), rel=2 * REL)
+
+
+def test_two_mixing_rounds_collapsed_into_one_table(psgd):
+    """Two randomized-ring rounds per step (more communication rounds per iteration) equal one
+    step with the 9-slot table of T_1 T_2."""
+    n, d = 32, 4100
+    n1, w1 = psgd.build_mixing(psgd.TOPO_RAND_RING, n, 5, 0)
+    n2, w2 = psgd.build_mixing(psgd.TOPO_RAND_RING, n, 5, 1)
+    nbr = np.zeros((n, 9), np.int32)
+    w = np.zeros((n, 9), np.float32)
+    for i in range(n):
+        for a in range(3):
+            j = n2[i, a]
+            for b in range(3):
+                nbr[i, 3 * a + b] = n1[j, b]
+                w[i, 3 * a + b] = w2[i, a] * w1[j, b]
+    assert np.allclose(orc.densify(nbr, w), orc.densify(n1, w1) @ orc.densify(n2, w2), atol=1e-7)
+    X = inp.host_normal_f32((n, d), 1.0, 7)
+    G = inp.host_normal_f32((n, d), 1.0, 8)
+    two = run_step(psgd, run_step(psgd, X, np.zeros_like(G), n1, w1, 0.0), G, n2, w2, 0.1)
+    one = run_step(psgd, X, G, nbr, w, 0.1)
+    assert_close(one, two.astype(np.float64), rel=3 * REL)
+    assert_close(one, orc.mix_step(X, G, orc.densify(nbr, w), 0.1), rel=3 * REL)
+
+
+def test_product_of_random_rings_contracts_as_predicted(psgd):
+    """Mixing the identity k times gives (T_1 ... T_k)^T itself.  Its distance from T_u must
+    match the oracle's dense product and, averaged over seeds, Sec. 3's expectation
+    (L-1) ((L-3)/(3(L-1)))^k (Eq. 11), which also bounds the spectral norm as in Eq. 12."""
+    n, k, trials = 16, 3, 150
+    Tu = orc.uniform_matrix(n)
+    eye = np.eye(n, dtype=np.float32)
+    zero = torch.zeros(n, n, device="cuda:0")
+    fro2, spec = [], []
+    for t in range(trials):
+        Xd = dev(eye)
+        P = np.eye(n)
+        for j in range(k):
+            nbr, w = psgd.build_mixing(psgd.TOPO_RAND_RING, n, 900 + t, j)
+            psgd.mix_step(Xd, Xd, zero, dev(nbr), dev(w), 0.0)
+            P = orc.densify(nbr, w).T @ P
+        got = Xd.cpu().numpy().astype(np.float64)
+        assert np.abs(got - P).max() <= 1e-6
+        fro2.append(np.linalg.norm(got - Tu, "fro") ** 2)
+        spec.append(np.linalg.norm(got - Tu, 2))
+    want = (n - 1) * ((n - 3) / (3 * (n - 1))) ** k
+    assert abs(np.mean(fro2) - want) < 5 * np.std(fro2) / np.sqrt(trials)
+    assert np.mean(spec) <= np.sqrt(n - 1) / np.sqrt(3) ** k
+
+
+def test_degree_table_out_of_range_is_flagged(psgd):
+    n, d, deg = 8, 1024, 4
+    rng = np.random.default_rng(1)
+    nbr, w = _perm_sum_table(n, deg, rng)
+    nbr[2, 3] = n
+    X = inp.host_normal_f32((n, d), 1.0, 1)
+    got, c = run_step_cd(psgd, X, X.copy(), nbr, w, 0.1)
+    assert np.isnan(got).all() and np.isnan(c) and psgd.device_status(clear=True) == 1
+
+
 # ------------------------------------------------------------------------- global averaging (T_u)
 @pytest.mark.parametrize("n,d", SHAPES)
 @pytest.mark.parametrize("gkind", ["f32", "bf16"])

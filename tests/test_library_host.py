@@ -106,6 +106,12 @@ def test_mix_step_argument_checks_need_no_device():
     assert lib.psgd_mix_step_cd(A, B, C, T1, T2, n, d, 0.1, 0, 0x3000004, None) == psgd.EALIGN
     assert lib.psgd_mix_step_cd(A, B, C, T1, T2, n, d, 0.1, 0, B + 8, None) == psgd.EALIAS
     assert lib.psgd_mix_step_cd_bf16g(A, A, C, T1, T2, n, d, 0.1, 1, 0x3000000, None) == psgd.EALIAS
+    dg = lib.psgd_mix_step_deg
+    assert dg(A, d, B, d, C, d, 0, T1, T2, 0, n, d, 0.1, 0, None, None) == psgd.EINVAL
+    assert dg(A, d, B, d, C, d, 0, T1, T2, 33, n, d, 0.1, 0, None, None) == psgd.EINVAL
+    assert dg(A, d, B, d, C, d, 0, T1, T2, 16, 512, d, 0.1, 0, None, None) == psgd.EINVAL      # n * deg too large
+    assert dg(A, d, A + 4, d, C, d, 0, T1, T2, 5, n, d, 0.1, 0, None, None) == psgd.EALIAS
+    assert dg(A, d, B, d, C, d, 0, T1, T2, 5, n, 0, 0.1, 0, None, None) == psgd.OK
     full = lib.psgd_mix_full
     assert full(A, d, B, d, C, d, 0, n, d, 0.1, 0, None, None) in (psgd.OK, psgd.EHIP)
     assert full(None, d, B, d, C, d, 0, n, d, 0.1, 0, None, None) == psgd.EINVAL
