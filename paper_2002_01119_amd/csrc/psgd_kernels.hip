@@ -31,6 +31,7 @@ constexpr int kTileBytes = 32 * 1024;  // LDS budget of the tiled path per workg
 constexpr int kUnroll = 8;           // rows whose loads are in flight together per lane
 constexpr int kMaxGrid = 4096;       // upper bound on persistent workgroups (scratch sizing)
 constexpr int kGridPerCu = 4;        // persistent workgroups per compute unit (16 waves per CU)
+constexpr size_t kDegLdsLimit = 96 * 1024;  // LDS a workgroup of the degree-K kernel may ask for (160 KB per CU)
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -104,13 +105,14 @@ struct Lds {
     float* w;
     char* scratch;
 };
+// (the ring entries exist only for 3-slot tables, the only ones that can take the ring walk)
 __host__ __device__ inline size_t lds_table_bytes(int n, int deg = 3) {
-    return (size_t)n * sizeof(RingEnt) + (size_t)n * deg * (sizeof(int) + sizeof(float));
+    return (deg == 3 ? (size_t)n * sizeof(RingEnt) : 0) + (size_t)n * deg * (sizeof(int) + sizeof(float));
 }
 __device__ __forceinline__ Lds carve(char* base, int n, int deg = 3) {
     Lds l;
     l.ring = reinterpret_cast<RingEnt*>(base);
-    l.nbr = reinterpret_cast<int*>(base + (size_t)n * sizeof(RingEnt));
+    l.nbr = reinterpret_cast<int*>(base + (deg == 3 ? (size_t)n * sizeof(RingEnt) : 0));
     l.w = reinterpret_cast<float*>(l.nbr + deg * n);
     // keep the scratch 16-byte aligned
     l.scratch = base + ((lds_table_bytes(n, deg) + 15) & ~(size_t)15);
@@ -334,10 +336,10 @@ __device__ __forceinline__ void ring_walk(const float* xc, float* oc, const GT* 
 // Tiled path for tables that are not a single ring.  The workgroup's 256 lanes form
 // (256 / lpr) row groups of lpr lanes; a tile is n rows by lpr column groups.
 // ---------------------------------------------------------------------------------------
-// Extra LDS of the tiled path when it also gathers the consensus statistics: one pivot per
-// column group and one (a, b) pair per lane for the combine across row groups.
-__host__ __device__ inline size_t tile_cd_bytes(int lpr, int vec) {
-    return (size_t)lpr * vec * sizeof(float) + 8 + (size_t)kThreads * 2 * vec * sizeof(double);
+// Extra LDS of the tiled path when it also gathers the consensus statistics: per lane its
+// pivot, sum and sum of squares for each of its VEC columns, and its row count.
+__host__ __device__ inline size_t tile_cd_bytes(int /*lpr*/, int vec) {
+    return 8 + (size_t)kThreads * (3 * vec + 1) * sizeof(double);
 }
 
 // One output group from the tile: slots in table order, acc = w0 * x0, then one fma per
@@ -356,8 +358,9 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
     typedef typename Cols<VEC>::T V;
     const Cols<VEC> tag{};
     V* tile = reinterpret_cast<V*>(l.scratch);
-    V* pivot = tile + (size_t)n * lpr;                          // [lpr]            (CD only)
-    double* comb = reinterpret_cast<double*>((reinterpret_cast<uintptr_t>(pivot + lpr) + 7) & ~(uintptr_t)7);  // [256][2 * VEC]
+    // [256][3 * VEC + 1] doubles (CD only), 8-byte aligned behind the tile
+    double* comb = reinterpret_cast<double*>((reinterpret_cast<uintptr_t>(tile + (size_t)n * lpr) + 7) & ~(uintptr_t)7);
+    constexpr int kRec = 3 * VEC + 1;
     const int lane = threadIdx.x % lpr, rg = threadIdx.x / lpr, nrg = kThreads / lpr;
     const int64_t ntiles = (ncg + lpr - 1) / lpr;
     double total = 0.0;
@@ -368,48 +371,50 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
         if (active)
             for (int r = rg; r < n; r += nrg) tile[r * lpr + lane] = ld_x(X + (int64_t)r * ld.x + col, tag);
         __syncthreads();
+        ColStats<VEC> stats;
+        int rows = 0;
+        if (CD) stats.reset();
         if (active)
             for (int r = rg; r < n; r += nrg) {
                 const V g = ld_g(G + (int64_t)r * ld.g + col, tag);
                 const V out = mix_slots<V>(tile, l.nbr + deg * r, l.w + deg * r, deg, lpr, lane, g, neg_lr);
                 st_x(Xout + (int64_t)r * ld.o + col, out);
-                if (CD && r == 0) pivot[lane] = out;
-            }
-        __syncthreads();
-        if (CD) {
-            // Second sweep over the intact tile: the same outputs again (G is read-only, so
-            // re-reading it is safe even when X_out aliases X), now measured against the
-            // column's pivot, then summed over the row groups in a fixed order.
-            double s[VEC], a[VEC], b[VEC];
-#pragma unroll
-            for (int k = 0; k < VEC; ++k) a[k] = b[k] = 0.0;
-            if (active) {
-                pivot_of(pivot[lane], s);
-                for (int r = rg; r < n; r += nrg) {
-                    if (r == 0) continue;
-                    const V g = ld_g(G + (int64_t)r * ld.g + col, tag);
-                    acc_diff<VEC>(a, b, mix_slots<V>(tile, l.nbr + deg * r, l.w + deg * r, deg, lpr, lane, g, neg_lr), s);
+                if (CD) {
+                    stats.add(out);
+                    ++rows;
                 }
             }
+        if (CD) {
+            // Each lane measured its rows against its own first output.  Lanes of one column
+            // group (one per row group) are merged by re-basing to the first lane's pivot:
+            // with delta = s_t - s,  sum' = sum_t + m_t delta,  sq' = sq_t + 2 delta sum_t + m_t delta^2.
+            double* rec = comb + (size_t)threadIdx.x * kRec;
 #pragma unroll
             for (int k = 0; k < VEC; ++k) {
-                comb[(size_t)threadIdx.x * 2 * VEC + k] = a[k];
-                comb[(size_t)threadIdx.x * 2 * VEC + VEC + k] = b[k];
+                rec[k] = rows ? stats.s[k] : 0.0;
+                rec[VEC + k] = stats.a[k];
+                rec[2 * VEC + k] = stats.b[k];
             }
+            rec[3 * VEC] = (double)rows;
             __syncthreads();
             if (active && rg == 0) {
 #pragma unroll
                 for (int k = 0; k < VEC; ++k) {
+                    const double s0 = comb[(size_t)lane * kRec + k];      // row group 0 always holds row 0
                     double at = 0.0, bt = 0.0;
                     for (int q = 0; q < nrg; ++q) {
-                        at += comb[(size_t)(q * lpr + lane) * 2 * VEC + k];
-                        bt += comb[(size_t)(q * lpr + lane) * 2 * VEC + VEC + k];
+                        const double* o = comb + (size_t)(q * lpr + lane) * kRec;
+                        const double m = o[3 * VEC];
+                        if (m == 0.0) continue;
+                        const double delta = o[k] - s0;
+                        at += o[VEC + k] + m * delta;
+                        bt += o[2 * VEC + k] + 2.0 * delta * o[VEC + k] + m * delta * delta;
                     }
                     total += bt - at * at * inv_n;
                 }
             }
-            __syncthreads();
         }
+        __syncthreads();
     }
     return total;
 }
@@ -600,13 +605,16 @@ __global__ __launch_bounds__(kThreads) void consensus_partial_kernel(const float
 // Fixed-order sum of the per-workgroup partials: lane t adds entries t, t+256, ... and the
 // 256 lane sums go through the same shuffle/LDS tree, so the result does not depend on
 // scheduling.
+// With poison_if_flagged the result is NaN while the sticky status word is raised (used when the
+// distance follows a step that may have refused its table and left X_out unwritten).
 __global__ __launch_bounds__(kThreads) void consensus_final_kernel(const double* __restrict__ partials, int count,
-                                                                   double* __restrict__ out) {
+                                                                   double* __restrict__ out,
+                                                                   int poison_if_flagged) {
     __shared__ double lds4[4];
     double v = 0.0;
     for (int i = threadIdx.x; i < count; i += kThreads) v += partials[i];
     const double bs = block_sum(v, lds4);
-    if (threadIdx.x == 0) out[0] = bs;
+    if (threadIdx.x == 0) out[0] = (poison_if_flagged && g_status_word != 0) ? __builtin_nan("") : bs;
 }
 
 __global__ __launch_bounds__(kThreads) void synth_grad_kernel(const float* __restrict__ xp,
@@ -744,6 +752,9 @@ int launch_mix(const DeviceInfo& di, size_t lds_bytes, hipStream_t s, const floa
     return grid;
 }
 
+int consensus_enqueue(const float* X, int64_t ldx, int n, int64_t d, double* out_dev, hipStream_t s,
+                      int poison_if_flagged = 0);
+
 // Pitches are in elements of the array they belong to.
 template <typename GT>
 int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, int64_t ldo, const GT* G, int64_t ldg,
@@ -782,11 +793,16 @@ int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
     if (d == 0) {
         if (!want_cd) return PSGD_OK;
         if (int rc = device_info(&di, true)) return rc;
-        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, di->scratch, 0, cd_out);
+        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, di->scratch, 0, cd_out, 0);
         const hipError_t e0 = hipGetLastError();
         return e0 == hipSuccess ? PSGD_OK : hip_fail(e0, "consensus_final_kernel");
     }
     if (int rc = device_info(&di, want_cd)) return rc;
+    // Tables that can only take the tiled path measure the distance with the separate
+    // read-only kernels afterwards: 4 more bytes per element at the (higher) read-only rate
+    // cost less than the tiled path's in-LDS merge of per-row-group statistics.
+    const bool cd_after = want_cd && deg != 3;
+    if (cd_after) want_cd = false;
 
     // 128-bit path needs every row start 16-byte aligned (8-byte for bf16 gradients).
     const bool vec4 = (d % 4 == 0) && (ldx % 4 == 0) && (ldo % 4 == 0) && (ldg % 4 == 0) && aligned_to(X, 16) &&
@@ -794,9 +810,9 @@ int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
     const int vec = vec4 ? 4 : 1;
     // Tile shape of the tiled path: widest power-of-two lane count whose tile (plus the
     // combine arrays of the fused distance) fits the budget and the 64 KB a workgroup may use.
-    const size_t lds_limit = 64 * 1024 - 64;
+    const size_t lds_limit = deg == 3 ? 64 * 1024 - 64 : kDegLdsLimit;   // wide tables may need more than 64 KB
     const size_t table_bytes = (lds_table_bytes(n, deg) + 15) & ~(size_t)15;
-    const size_t tile_budget = want_cd ? (size_t)kTileBytes / 2 : (size_t)kTileBytes;
+    const size_t tile_budget = (size_t)kTileBytes;
     int lpr = 64;
     size_t scratch_bytes = 0;
     for (;; lpr >>= 1) {
@@ -814,9 +830,19 @@ int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
     int grid = 0;
     if (deg != 3) {
         const int64_t ntiles = (d / vec + lpr - 1) / lpr;
-        const int64_t cap = (int64_t)di->cus * 2;
+        int per_cu = (int)((size_t)(160 * 1024) / (lds_bytes + 512));     // what the 160 KB of LDS per CU admit
+        if (per_cu > 2 * kGridPerCu) per_cu = 2 * kGridPerCu;
+        if (per_cu < 1) per_cu = 1;
+        const int64_t cap = (int64_t)di->cus * per_cu;
         grid = (int)(ntiles < cap ? ntiles : cap);
         const dim3 g(grid), b(kThreads);
+        if (lds_bytes > 64 * 1024 - 64) {
+            // opt in to more than the default 64 KB of dynamic LDS (once per instantiation is enough, but the call is cheap)
+            const void* fn = vec4 ? (want_cd ? (const void*)mix_deg_kernel<4, GT, true> : (const void*)mix_deg_kernel<4, GT, false>)
+                                  : (want_cd ? (const void*)mix_deg_kernel<1, GT, true> : (const void*)mix_deg_kernel<1, GT, false>);
+            const hipError_t ea = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDegLdsLimit);
+            if (ea != hipSuccess) return hip_fail(ea, "hipFuncSetAttribute(MaxDynamicSharedMemorySize)");
+        }
         if (vec4 && want_cd)
             hipLaunchKernelGGL((mix_deg_kernel<4, GT, true>), g, b, lds_bytes, s, X, X_out, G, nbr, w, deg, n, d, ld,
                                neg_lr, lpr, partials);
@@ -840,10 +866,11 @@ int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, name);
     if (want_cd) {
-        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, partials, grid, cd_out);
+        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, partials, grid, cd_out, 0);
         e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e, "consensus_final_kernel");
     }
+    if (cd_after) return consensus_enqueue(X_out, ldo, n, d, cd_out, s, 1);
     return PSGD_OK;
 }
 
@@ -880,7 +907,7 @@ int mix_full_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
     if (d == 0) {
         if (!want_cd) return PSGD_OK;
         if (int rc = device_info(&di, true)) return rc;
-        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, di->scratch, 0, cd_out);
+        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, di->scratch, 0, cd_out, 0);
         const hipError_t e0 = hipGetLastError();
         return e0 == hipSuccess ? PSGD_OK : hip_fail(e0, "consensus_final_kernel");
     }
@@ -903,14 +930,15 @@ int mix_full_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, name);
     if (want_cd) {
-        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, partials, grid, cd_out);
+        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, partials, grid, cd_out, 0);
         e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e, "consensus_final_kernel");
     }
     return PSGD_OK;
 }
 
-int consensus_enqueue(const float* X, int64_t ldx, int n, int64_t d, double* out_dev, hipStream_t s) {
+int consensus_enqueue(const float* X, int64_t ldx, int n, int64_t d, double* out_dev, hipStream_t s,
+                      int poison_if_flagged) {
     DeviceInfo* di = nullptr;
     if (int rc = device_info(&di, true)) return rc;
     const bool vec4 = (d % 4 == 0) && (ldx % 4 == 0) && aligned_to(X, 16);
@@ -922,7 +950,7 @@ int consensus_enqueue(const float* X, int64_t ldx, int n, int64_t d, double* out
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "consensus_partial_kernel");
     hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, di->scratch, grid,
-                       out_dev ? out_dev : di->scratch + kMaxGrid);
+                       out_dev ? out_dev : di->scratch + kMaxGrid, poison_if_flagged);
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "consensus_final_kernel");
     return PSGD_OK;
@@ -949,7 +977,7 @@ int consensus_async_impl(const char* name, const float* X, int64_t ldx, int n, i
         // nothing to reduce: the final kernel over zero partials writes 0
         DeviceInfo* di = nullptr;
         if (int rc = device_info(&di, true)) return rc;
-        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, di->scratch, 0, out_dev);
+        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, di->scratch, 0, out_dev, 0);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e, "consensus_final_kernel");
         return PSGD_OK;
