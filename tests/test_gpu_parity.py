@@ -612,3 +612,48 @@ def test_mean_preserved_at_zero_lr(psgd):
     m0 = X0.astype(np.float64).mean(0)
     m1 = Xd.cpu().numpy().astype(np.float64).mean(0)
     assert np.abs(m1 - m0).max() <= steps * 1e-7 * np.abs(m0).max()
+
+
+# ------------------------------------------------------------------------- HIP graph capture
+def test_steps_captured_in_a_hip_graph_replay_exactly(psgd):
+    """The step only enqueues kernels (no allocation once the scratch exists, no memset), so a
+    run of steps with pre-uploaded tables can be captured once and replayed.  Replays are
+    interleaved with eager work and compared with the eager result every time."""
+    n, d, steps = 16, 40_004, 4
+    X0 = inp.host_normal_f32((n, d), 1.0, 21)
+    Gh = inp.host_normal_f32((n, d), 0.1, 22)
+    tabs = [psgd.build_mixing(psgd.TOPO_RAND_RING, n, 33, k) for k in range(steps)]
+    nbr_d = [dev(t[0]) for t in tabs]
+    w_d = [dev(t[1]) for t in tabs]
+    G = dev(Gh)
+    c_eager = torch.zeros(steps, dtype=torch.float64, device="cuda:0")
+    c_graph = torch.zeros(steps, dtype=torch.float64, device="cuda:0")
+    A, B = dev(X0), torch.empty(n, d, device="cuda:0")
+
+    def run(cbuf, stream=None):
+        src, dst = A, B
+        for k in range(steps):
+            psgd.mix_step(src, dst, G, nbr_d[k], w_d[k], 0.05, cdist_out=cbuf[k:k + 1], stream=stream)
+            src, dst = dst, src
+        return src
+
+    final = run(c_eager)                       # also allocates the library's scratch before capture
+    torch.cuda.synchronize()
+    want = final.clone()
+    s = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    A.copy_(dev(X0))
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g, stream=s):
+        out = run(c_graph, stream=torch.cuda.current_stream())
+    for rep in range(3):
+        A.copy_(dev(X0))
+        B.fill_(float("nan"))
+        c_graph.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), rep
+        assert torch.equal(c_graph, c_eager), rep
+        # eager work of the same library between replays
+        assert abs(psgd.consensus_dist(out) - c_eager[-1].item()) <= 1e-9 * c_eager[-1].item()
