@@ -90,6 +90,9 @@ def main():
     ap.add_argument("--global-average", action="store_true",
                     help="mix with T_u = (1/n) 1 1^T (psgd_mix_full: S-PSGD / the paper's own D1D-PSGD) instead of "
                          "the workload's ring table")
+    ap.add_argument("--degree", type=int, default=3,
+                    help="odd K > 3: mix with K neighbours on the workload's ring (self and (K-1)/2 learners on each "
+                         "side, weight 1/K each) through psgd_mix_step_deg, the general sparse-table kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layout", choices=["pitched", "probe", "dense"], default="pitched",
                     help="where the arrays live in HBM: 'pitched' interleaves the rows of all arrays across most of "
@@ -101,6 +104,9 @@ def main():
                     help="before the warm-up, run a plain dense device copy of known size (printed); under "
                          "rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE readings calibrate the mix kernel's")
     args = ap.parse_args()
+    if args.degree < 3 or args.degree % 2 == 0 or (args.degree > 3 and args.global_average):
+        log("bench.py: --degree takes an odd K >= 3 and excludes --global-average")
+        sys.exit(2)
     if args.gpus != 1:
         log("bench.py: this build runs all learners on ONE GPU (no collectives); --gpus %d is not "
             "supported, run with --gpus 1" % args.gpus)
@@ -188,10 +194,14 @@ def main():
     if wl.delay:
         X_prev = views["Xprev"] if (views is not None and "Xprev" in views) else torch.empty((n, d), device=dev)
         X_prev.copy_(X)
-    nbr_host = torch.empty((total, n, 3), dtype=torch.int32, pin_memory=True)
-    w_host = torch.empty((total, n, 3), dtype=torch.float32, pin_memory=True)
-    nbr_dev = torch.empty((total, n, 3), dtype=torch.int32, device=dev)
-    w_dev = torch.empty((total, n, 3), dtype=torch.float32, device=dev)
+    deg = args.degree
+    if deg > min(n, 32) or n * deg > 4096:
+        log("bench.py: --degree %d does not fit n = %d" % (deg, n))
+        sys.exit(2)
+    nbr_host = torch.empty((total, n, deg), dtype=torch.int32, pin_memory=True)
+    w_host = torch.empty((total, n, deg), dtype=torch.float32, pin_memory=True)
+    nbr_dev = torch.empty((total, n, deg), dtype=torch.int32, device=dev)
+    w_dev = torch.empty((total, n, deg), dtype=torch.float32, device=dev)
     cdist = torch.zeros(total, dtype=torch.float64, device=dev)
     stream = torch.cuda.Stream(device=dev)
     ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(total)]
@@ -204,9 +214,21 @@ def main():
         ev_prod[0].record(stream2)
     torch.cuda.synchronize()
 
+    def widen(nbr3):
+        """K-slot table on the same ring: follow the right (left) pointers (K-1)/2 times."""
+        left, right = nbr3[:, 1], nbr3[:, 2]
+        cols, lo, hi = [nbr3[:, 0]], nbr3[:, 0], nbr3[:, 0]
+        for _ in range((deg - 1) // 2):
+            lo, hi = left[lo], right[hi]
+            cols += [lo, hi]
+        return (np.ascontiguousarray(np.stack(cols, axis=1), dtype=np.int32),
+                np.full((n, deg), 1.0 / deg, dtype=np.float32))
+
     def one_step(k):
         nonlocal X, Y, X_prev
         nbr, w = psgd.build_mixing(wl.topology, n, wl.seed_perm, k)
+        if deg > 3:
+            nbr, w = widen(nbr)
         nbr_host[k].copy_(torch.from_numpy(nbr))
         w_host[k].copy_(torch.from_numpy(w))
         nbr_dev[k].copy_(nbr_host[k], non_blocking=True)
@@ -308,6 +330,7 @@ def main():
         "config": {
             "workload": wl.name, "n": n, "d": d, "g_dtype": wl.g_dtype,
             "topology": "full (T_u)" if args.global_average else {0: "ring", 1: "rand_ring"}[wl.topology],
+            "table_degree": deg,
             "lr": wl.lr,
             "delay_by_one": wl.delay, "consensus_every_step": not args.no_consensus,
             "consensus_fused_into_mix_kernel": fused,
@@ -315,11 +338,12 @@ def main():
             "hbm_layout": layout_report,
         },
         "roofline": {
-            "kernel": ("mix_full_kernel" if args.global_average else "mix_step_kernel")
+            "kernel": ("mix_full_kernel" if args.global_average else "mix_deg_kernel" if deg > 3
+                       else "mix_step_kernel")
                       + (" (with fused consensus statistics)" if fused else ""),
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-            "traffic": None if args.global_average else MEASURED_TRAFFIC_BYTES.get(wl.name),
+            "traffic": None if (args.global_average or deg > 3) else MEASURED_TRAFFIC_BYTES.get(wl.name),
             "algorithmic_bytes_per_launch": mix_bytes, "avg_launch_ms": mix_avg,
         },
         "mix_updates_per_s": n * d / (mix_avg * 1e-3),

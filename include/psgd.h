@@ -166,10 +166,8 @@ int psgd_mix_step_ex(const float* X, int64_t ldx, float* X_out, int64_t ldo,
  * n * deg <= PSGD_MAX_TABLE.  Per element: acc = w0 * x0; acc = fma(w_s, x_s, acc) for
  * s = 1..deg-1 in table order; out = fma(-lr, g, acc).  deg = 3 is psgd_mix_step_ex (ring
  * tables then take the register walk); other degrees always stage an [n x columns] tile in
- * LDS.  Everything else (pitches, gradient type, in-place rule, cdist_out, errors) is as in
- * psgd_mix_step_ex, except that for deg != 3 the distance is measured by the read-only kernels
- * of psgd_consensus_dist_ex right after the step (bit-identical to calling that yourself),
- * and is NaN for as long as the flag of psgd_device_status() is raised.
+ * LDS.  Everything else (pitches, gradient type, in-place rule, cdist_out gathered in the same
+ * pass, errors) is as in psgd_mix_step_ex.
  */
 int psgd_mix_step_deg(const float* X, int64_t ldx, float* X_out, int64_t ldo,
                       const void* G, int64_t ldg, int g_is_bf16,

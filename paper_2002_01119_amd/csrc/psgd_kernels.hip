@@ -29,6 +29,8 @@ namespace {
 constexpr int kThreads = 256;        // 4 wavefronts of 64 lanes
 constexpr int kTileBytes = 32 * 1024;  // LDS budget of the tiled path per workgroup
 constexpr int kUnroll = 8;           // rows whose loads are in flight together per lane
+constexpr int kTileUnroll = 4;     // rows whose loads a lane of the tiled path keeps in flight (8 would cost a
+                                   // resident workgroup per CU in registers, which this path needs more)
 constexpr int kMaxGrid = 4096;       // upper bound on persistent workgroups (scratch sizing)
 constexpr int kGridPerCu = 4;        // persistent workgroups per compute unit (16 waves per CU)
 constexpr size_t kDegLdsLimit = 96 * 1024;  // LDS a workgroup of the degree-K kernel may ask for (160 KB per CU)
@@ -99,21 +101,32 @@ struct __attribute__((aligned(16))) RingEnt {
 
 // LDS carve-up (dynamic, sized by the launcher):
 //   RingEnt ring[n] | int nbr[3n] | float w[3n] | scratch (ranking arrays or the data tile)
+// Tables with another slot count never take the ring walk; they keep only
+//   float w[deg n] | uint16 nbr16[deg n] | scratch (the data tile)
+// (n <= 512 fits 16 bits; the 2 bytes saved per slot decide whether a fourth workgroup fits a CU).
 struct Lds {
     RingEnt* ring;
     int* nbr;
+    uint16_t* nbr16;
     float* w;
     char* scratch;
 };
-// (the ring entries exist only for 3-slot tables, the only ones that can take the ring walk)
 __host__ __device__ inline size_t lds_table_bytes(int n, int deg = 3) {
-    return (deg == 3 ? (size_t)n * sizeof(RingEnt) : 0) + (size_t)n * deg * (sizeof(int) + sizeof(float));
+    return deg == 3 ? (size_t)n * (sizeof(RingEnt) + 3 * (sizeof(int) + sizeof(float)))
+                    : (size_t)n * deg * (sizeof(float) + sizeof(uint16_t));
 }
 __device__ __forceinline__ Lds carve(char* base, int n, int deg = 3) {
     Lds l;
     l.ring = reinterpret_cast<RingEnt*>(base);
-    l.nbr = reinterpret_cast<int*>(base + (deg == 3 ? (size_t)n * sizeof(RingEnt) : 0));
-    l.w = reinterpret_cast<float*>(l.nbr + deg * n);
+    if (deg == 3) {
+        l.nbr = reinterpret_cast<int*>(base + (size_t)n * sizeof(RingEnt));
+        l.w = reinterpret_cast<float*>(l.nbr + 3 * n);
+        l.nbr16 = nullptr;
+    } else {
+        l.nbr = nullptr;
+        l.w = reinterpret_cast<float*>(base);
+        l.nbr16 = reinterpret_cast<uint16_t*>(l.w + deg * n);
+    }
     // keep the scratch 16-byte aligned
     l.scratch = base + ((lds_table_bytes(n, deg) + 15) & ~(size_t)15);
     return l;
@@ -336,31 +349,40 @@ __device__ __forceinline__ void ring_walk(const float* xc, float* oc, const GT* 
 // Tiled path for tables that are not a single ring.  The workgroup's 256 lanes form
 // (256 / lpr) row groups of lpr lanes; a tile is n rows by lpr column groups.
 // ---------------------------------------------------------------------------------------
-// Extra LDS of the tiled path when it also gathers the consensus statistics: per lane its
-// pivot, sum and sum of squares for each of its VEC columns, and its row count.
-__host__ __device__ inline size_t tile_cd_bytes(int /*lpr*/, int vec) {
-    return 8 + (size_t)kThreads * (3 * vec + 1) * sizeof(double);
+// Extra LDS of the tiled path when it also gathers the consensus statistics: one partial
+// column sum per wavefront and column.
+__host__ __device__ inline size_t tile_cd_bytes(int lpr, int vec) {
+    return 8 + (size_t)(kThreads / 64) * lpr * vec * sizeof(double);
 }
 
 // One output group from the tile: slots in table order, acc = w0 * x0, then one fma per
 // further slot, then the gradient term (for 3 slots this is exactly mix_one's order).
-template <typename V>
-__device__ __forceinline__ V mix_slots(const V* tile, const int* nbr, const float* w, int deg, int lpr, int lane, V g,
+template <typename V, typename IT>
+__device__ __forceinline__ V mix_slots(const V* tile, const IT* nbr, const float* w, int deg, int lpr, int lane, V g,
                                        float neg_lr) {
     V acc = tile[nbr[0] * lpr + lane] * w[0];
     for (int s = 1; s < deg; ++s) acc = vfma(w[s], tile[nbr[s] * lpr + lane], acc);
     return vfma(neg_lr, g, acc);
 }
 
-template <int VEC, typename GT, bool CD>
-__device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ G, const Lds& l,
+// A lane's rows are rg, rg + nrg, ...; they are handled kTileUnroll at a time: that many loads
+// are in flight together, and the table look-ups and tile reads of that many rows (independent
+// chains of two dependent LDS reads per slot) interleave instead of queueing behind each other.
+//
+// With CD the distance of the outputs is gathered in the same pass.  The rows of one column
+// group are spread over the row groups, so all of them measure against ONE pivot, the output
+// of row 0, which every row group computes for itself (bit-identical: same tile, same table,
+// same gradient bits; the extra read of G's row 0 is served by the cache).  The squares then
+// add up lane by lane and only the plain sums need merging per column, through LDS.
+template <int VEC, typename GT, bool CD, typename IT>
+__device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ G, const Lds& l, const IT* nbr_tab,
                             int n, Pitch ld, int64_t ncg, float neg_lr, int lpr, double inv_n, int deg = 3) {
     typedef typename Cols<VEC>::T V;
     const Cols<VEC> tag{};
+    constexpr int U = kTileUnroll;
     V* tile = reinterpret_cast<V*>(l.scratch);
-    // [256][3 * VEC + 1] doubles (CD only), 8-byte aligned behind the tile
+    // [4 wavefronts][lpr][VEC] doubles (CD only), 8-byte aligned behind the tile
     double* comb = reinterpret_cast<double*>((reinterpret_cast<uintptr_t>(tile + (size_t)n * lpr) + 7) & ~(uintptr_t)7);
-    constexpr int kRec = 3 * VEC + 1;
     const int lane = threadIdx.x % lpr, rg = threadIdx.x / lpr, nrg = kThreads / lpr;
     const int64_t ntiles = (ncg + lpr - 1) / lpr;
     double total = 0.0;
@@ -368,53 +390,87 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
         const int64_t cg = t * lpr + lane;
         const bool active = cg < ncg;
         const int64_t col = cg * VEC;
-        if (active)
-            for (int r = rg; r < n; r += nrg) tile[r * lpr + lane] = ld_x(X + (int64_t)r * ld.x + col, tag);
-        __syncthreads();
-        ColStats<VEC> stats;
-        int rows = 0;
-        if (CD) stats.reset();
-        if (active)
-            for (int r = rg; r < n; r += nrg) {
-                const V g = ld_g(G + (int64_t)r * ld.g + col, tag);
-                const V out = mix_slots<V>(tile, l.nbr + deg * r, l.w + deg * r, deg, lpr, lane, g, neg_lr);
-                st_x(Xout + (int64_t)r * ld.o + col, out);
-                if (CD) {
-                    stats.add(out);
-                    ++rows;
+        // The gradients of the first batch and of row 0 (for the pivot) do not depend on the
+        // tile: requested before the barrier, their latency hides behind the tile's load.
+        V gs[U], g0 = {};
+        if (active) {
+            if (CD) g0 = ld_g(G + col, tag);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int r = rg + u * nrg;
+                if (r < n) gs[u] = ld_g(G + (int64_t)r * ld.g + col, tag);
+            }
+            for (int r0 = rg; r0 < n; r0 += kTileUnroll * nrg) {
+                V xs[kTileUnroll];
+#pragma unroll
+                for (int u = 0; u < kTileUnroll; ++u) {
+                    const int r = r0 + u * nrg;
+                    if (r < n) xs[u] = ld_x(X + (int64_t)r * ld.x + col, tag);
                 }
-            }
-        if (CD) {
-            // Each lane measured its rows against its own first output.  Lanes of one column
-            // group (one per row group) are merged by re-basing to the first lane's pivot:
-            // with delta = s_t - s,  sum' = sum_t + m_t delta,  sq' = sq_t + 2 delta sum_t + m_t delta^2.
-            double* rec = comb + (size_t)threadIdx.x * kRec;
 #pragma unroll
-            for (int k = 0; k < VEC; ++k) {
-                rec[k] = rows ? stats.s[k] : 0.0;
-                rec[VEC + k] = stats.a[k];
-                rec[2 * VEC + k] = stats.b[k];
-            }
-            rec[3 * VEC] = (double)rows;
-            __syncthreads();
-            if (active && rg == 0) {
-#pragma unroll
-                for (int k = 0; k < VEC; ++k) {
-                    const double s0 = comb[(size_t)lane * kRec + k];      // row group 0 always holds row 0
-                    double at = 0.0, bt = 0.0;
-                    for (int q = 0; q < nrg; ++q) {
-                        const double* o = comb + (size_t)(q * lpr + lane) * kRec;
-                        const double m = o[3 * VEC];
-                        if (m == 0.0) continue;
-                        const double delta = o[k] - s0;
-                        at += o[VEC + k] + m * delta;
-                        bt += o[2 * VEC + k] + 2.0 * delta * o[VEC + k] + m * delta * delta;
-                    }
-                    total += bt - at * at * inv_n;
+                for (int u = 0; u < kTileUnroll; ++u) {
+                    const int r = r0 + u * nrg;
+                    if (r < n) tile[r * lpr + lane] = xs[u];
                 }
             }
         }
         __syncthreads();
+        double piv[VEC], a[VEC], sq = 0.0;
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) piv[k] = a[k] = 0.0;
+        if (active) {
+            if (CD) pivot_of(mix_slots<V>(tile, nbr_tab, l.w, deg, lpr, lane, g0, neg_lr), piv);
+            for (int r0 = rg; r0 < n; r0 += U * nrg) {
+                if (r0 != rg) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int r = r0 + u * nrg;
+                        if (r < n) gs[u] = ld_g(G + (int64_t)r * ld.g + col, tag);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int r = r0 + u * nrg;
+                    if (r < n) {
+                        const V out = mix_slots<V>(tile, nbr_tab + deg * r, l.w + deg * r, deg, lpr, lane, gs[u], neg_lr);
+                        st_x(Xout + (int64_t)r * ld.o + col, out);
+                        if (CD) {
+                            double o[VEC];
+                            pivot_of(out, o);      // widen
+#pragma unroll
+                            for (int k = 0; k < VEC; ++k) {
+                                const double df = o[k] - piv[k];
+                                a[k] += df;
+                                sq = fma(df, df, sq);
+                            }
+                        }
+                    }
+                }
+            }
+        }
+        if (CD) {
+            // Column sums: first across the row groups that share a wavefront (lanes lpr apart hold
+            // the same columns; the exchange is symmetric, so all of them end with the same bits),
+            // then one slot per wavefront in LDS.
+            const int wl = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) {
+                for (int off = lpr; off < 64; off <<= 1) a[k] += __shfl_xor(a[k], off, 64);
+                if (wl < lpr) comb[(size_t)(wave * lpr + wl) * VEC + k] = a[k];
+            }
+            total += sq;
+        }
+        // Every read of the tile is done: the next sweep may overwrite it.  (The merge below reads
+        // only `comb`, which is not written again before the barrier that follows the next load.)
+        __syncthreads();
+        if (CD && active && rg == 0) {
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) {
+                const double at = (comb[(size_t)lane * VEC + k] + comb[(size_t)(lpr + lane) * VEC + k]) +
+                                  (comb[(size_t)(2 * lpr + lane) * VEC + k] + comb[(size_t)(3 * lpr + lane) * VEC + k]);
+                total -= at * at * inv_n;
+            }
+        }
     }
     return total;
 }
@@ -449,7 +505,7 @@ __global__ __launch_bounds__(kThreads) void mix_step_kernel(const float* X, floa
             if (CD) total += stats.result(inv_n);
         }
     } else {
-        total = tile_path<VEC, GT, CD>(X, Xout, G, l, n, ld, ncg, neg_lr, lpr, inv_n);
+        total = tile_path<VEC, GT, CD>(X, Xout, G, l, l.nbr, n, ld, ncg, neg_lr, lpr, inv_n);
     }
     if (CD) {
         const double bs = block_sum(total, lds4);
@@ -460,7 +516,7 @@ __global__ __launch_bounds__(kThreads) void mix_step_kernel(const float* X, floa
 // Any table with `deg` slots per row (sparse doubly stochastic matrices beyond the ring:
 // more neighbours, lazy walks, products of several mixing rounds).  Always the tiled path.
 template <int VEC, typename GT, bool CD>
-__global__ __launch_bounds__(kThreads) void mix_deg_kernel(const float* X, float* Xout, const GT* __restrict__ G,
+__global__ __launch_bounds__(kThreads, 4) void mix_deg_kernel(const float* X, float* Xout, const GT* __restrict__ G,
                                                            const int32_t* __restrict__ nbr,
                                                            const float* __restrict__ w, int deg, int n, int64_t d,
                                                            Pitch ld, float neg_lr, int lpr,
@@ -471,7 +527,7 @@ __global__ __launch_bounds__(kThreads) void mix_deg_kernel(const float* X, float
     int ok = 1;
     for (int e = threadIdx.x; e < deg * n; e += kThreads) {
         const int v = nbr[e];
-        l.nbr[e] = v;
+        l.nbr16[e] = (uint16_t)v;
         l.w[e] = w[e];
         ok &= (unsigned)v < (unsigned)n;
     }
@@ -480,7 +536,7 @@ __global__ __launch_bounds__(kThreads) void mix_deg_kernel(const float* X, float
         if (CD && threadIdx.x == 0) partials[blockIdx.x] = __builtin_nan("");
         return;
     }
-    const double total = tile_path<VEC, GT, CD>(X, Xout, G, l, n, ld, d / VEC, neg_lr, lpr, 1.0 / (double)n, deg);
+    const double total = tile_path<VEC, GT, CD>(X, Xout, G, l, l.nbr16, n, ld, d / VEC, neg_lr, lpr, 1.0 / (double)n, deg);
     if (CD) {
         const double bs = block_sum(total, lds4);
         if (threadIdx.x == 0) partials[blockIdx.x] = bs;
@@ -605,16 +661,13 @@ __global__ __launch_bounds__(kThreads) void consensus_partial_kernel(const float
 // Fixed-order sum of the per-workgroup partials: lane t adds entries t, t+256, ... and the
 // 256 lane sums go through the same shuffle/LDS tree, so the result does not depend on
 // scheduling.
-// With poison_if_flagged the result is NaN while the sticky status word is raised (used when the
-// distance follows a step that may have refused its table and left X_out unwritten).
 __global__ __launch_bounds__(kThreads) void consensus_final_kernel(const double* __restrict__ partials, int count,
-                                                                   double* __restrict__ out,
-                                                                   int poison_if_flagged) {
+                                                                   double* __restrict__ out) {
     __shared__ double lds4[4];
     double v = 0.0;
     for (int i = threadIdx.x; i < count; i += kThreads) v += partials[i];
     const double bs = block_sum(v, lds4);
-    if (threadIdx.x == 0) out[0] = (poison_if_flagged && g_status_word != 0) ? __builtin_nan("") : bs;
+    if (threadIdx.x == 0) out[0] = bs;
 }
 
 __global__ __launch_bounds__(kThreads) void synth_grad_kernel(const float* __restrict__ xp,
@@ -722,29 +775,44 @@ bool rows_overlap(const void* A, int64_t lda, size_t ra, const void* B, int64_t 
     return false;
 }
 
+// Workgroups of `fn` (256 threads, `lds_bytes` of dynamic LDS) that fit one compute unit, as the
+// runtime computes it from the kernel's registers and LDS; remembered per (kernel, LDS size).
+int resident_per_cu(const void* fn, size_t lds_bytes) {
+    struct Entry {
+        const void* fn;
+        size_t lds;
+        int occ;
+    };
+    static std::mutex mu;
+    static Entry cache[32];
+    static int used = 0;
+    std::lock_guard<std::mutex> lock(mu);
+    for (int i = 0; i < used; ++i)
+        if (cache[i].fn == fn && cache[i].lds == lds_bytes) return cache[i].occ;
+    int q = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&q, fn, kThreads, lds_bytes) != hipSuccess || q < 1) q = 1;
+    if (used < 32) cache[used++] = Entry{fn, lds_bytes, q};
+    return q;
+}
+
+// True if the double at p shares a byte with any row of B.
+bool scalar_overlaps(const double* p, const void* B, int64_t ldb, size_t rb, int n) {
+    const uintptr_t p0 = reinterpret_cast<uintptr_t>(p), b0 = reinterpret_cast<uintptr_t>(B);
+    for (int j = 0; j < n; ++j) {
+        const uintptr_t bj = b0 + (uintptr_t)j * (uintptr_t)ldb;
+        if (p0 < bj + rb && bj < p0 + sizeof(double)) return true;
+    }
+    return false;
+}
+
 // Launches one instantiation of the mix kernel on a persistent grid sized to what is
 // actually resident: min(kGridPerCu, occupancy for this LDS size) workgroups per CU.
-// Returns the grid size.  The occupancy query is cached per instantiation and LDS size.
+// Returns the grid size.
 template <int VEC, typename GT, bool CD>
 int launch_mix(const DeviceInfo& di, size_t lds_bytes, hipStream_t s, const float* X, float* X_out, const GT* G,
                const int32_t* nbr, const float* w, int n, int64_t d, Pitch ld, float neg_lr, int lpr,
                double* partials) {
-    static std::mutex mu;
-    static size_t cached_lds = ~(size_t)0;
-    static int cached_occ = 0;
-    int occ = 0;
-    {
-        std::lock_guard<std::mutex> lock(mu);
-        if (cached_lds != lds_bytes) {
-            int q = 0;
-            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&q, mix_step_kernel<VEC, GT, CD>, kThreads, lds_bytes) !=
-                    hipSuccess || q < 1)
-                q = 1;
-            cached_occ = q;
-            cached_lds = lds_bytes;
-        }
-        occ = cached_occ;
-    }
+    const int occ = resident_per_cu(reinterpret_cast<const void*>(mix_step_kernel<VEC, GT, CD>), lds_bytes);
     const int per_cu = occ < kGridPerCu ? occ : kGridPerCu;
     const int grid = persistent_grid(di, d / VEC, per_cu);
     hipLaunchKernelGGL((mix_step_kernel<VEC, GT, CD>), dim3(grid), dim3(kThreads), lds_bytes, s, X, X_out, G, nbr, w, n,
@@ -752,8 +820,7 @@ int launch_mix(const DeviceInfo& di, size_t lds_bytes, hipStream_t s, const floa
     return grid;
 }
 
-int consensus_enqueue(const float* X, int64_t ldx, int n, int64_t d, double* out_dev, hipStream_t s,
-                      int poison_if_flagged = 0);
+int consensus_enqueue(const float* X, int64_t ldx, int n, int64_t d, double* out_dev, hipStream_t s);
 
 // Pitches are in elements of the array they belong to.
 template <typename GT>
@@ -785,25 +852,19 @@ int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
         return fail(PSGD_EALIAS, "%s: X_out partially overlaps X", name);
     }
     if (rows_overlap(G, bg, grow, X_out, bo, xrow, n)) return fail(PSGD_EALIAS, "%s: X_out overlaps G", name);
-    if (want_cd && (rows_overlap(cd_out, 8, 8, X_out, bo, xrow, n) || rows_overlap(cd_out, 8, 8, X, bx, xrow, n) ||
-                    rows_overlap(cd_out, 8, 8, G, bg, grow, n)))
+    if (want_cd && (scalar_overlaps(cd_out, X_out, bo, xrow, n) || scalar_overlaps(cd_out, X, bx, xrow, n) ||
+                    scalar_overlaps(cd_out, G, bg, grow, n)))
         return fail(PSGD_EALIAS, "%s: the distance output overlaps a data buffer", name);
     hipStream_t s = static_cast<hipStream_t>(stream);
     DeviceInfo* di = nullptr;
     if (d == 0) {
         if (!want_cd) return PSGD_OK;
         if (int rc = device_info(&di, true)) return rc;
-        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, di->scratch, 0, cd_out, 0);
+        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, di->scratch, 0, cd_out);
         const hipError_t e0 = hipGetLastError();
         return e0 == hipSuccess ? PSGD_OK : hip_fail(e0, "consensus_final_kernel");
     }
     if (int rc = device_info(&di, want_cd)) return rc;
-    // Tables that can only take the tiled path measure the distance with the separate
-    // read-only kernels afterwards: 4 more bytes per element at the (higher) read-only rate
-    // cost less than the tiled path's in-LDS merge of per-row-group statistics.
-    const bool cd_after = want_cd && deg != 3;
-    if (cd_after) want_cd = false;
-
     // 128-bit path needs every row start 16-byte aligned (8-byte for bf16 gradients).
     const bool vec4 = (d % 4 == 0) && (ldx % 4 == 0) && (ldo % 4 == 0) && (ldg % 4 == 0) && aligned_to(X, 16) &&
                       aligned_to(X_out, 16) && aligned_to(G, 4 * sizeof(GT));
@@ -822,7 +883,8 @@ int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
     }
     if (scratch_bytes < (size_t)n * 4 * sizeof(int)) scratch_bytes = (size_t)n * 4 * sizeof(int);
     const size_t lds_bytes = table_bytes + scratch_bytes;
-    if (lds_bytes > lds_limit) return fail(PSGD_EINVAL, "%s: n=%d, deg=%d needs %zu bytes of LDS", name, n, deg, lds_bytes);
+    if (lds_bytes > lds_limit)
+        return fail(PSGD_EINVAL, "%s: n=%d, deg=%d needs %zu bytes of LDS", name, n, deg, lds_bytes);
 
     const float neg_lr = -lr;
     const Pitch ld{ldx, ldo, ldg};
@@ -830,19 +892,18 @@ int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
     int grid = 0;
     if (deg != 3) {
         const int64_t ntiles = (d / vec + lpr - 1) / lpr;
-        int per_cu = (int)((size_t)(160 * 1024) / (lds_bytes + 512));     // what the 160 KB of LDS per CU admit
-        if (per_cu > 2 * kGridPerCu) per_cu = 2 * kGridPerCu;
-        if (per_cu < 1) per_cu = 1;
-        const int64_t cap = (int64_t)di->cus * per_cu;
-        grid = (int)(ntiles < cap ? ntiles : cap);
-        const dim3 g(grid), b(kThreads);
+        const void* fn = vec4 ? (want_cd ? (const void*)mix_deg_kernel<4, GT, true> : (const void*)mix_deg_kernel<4, GT, false>)
+                              : (want_cd ? (const void*)mix_deg_kernel<1, GT, true> : (const void*)mix_deg_kernel<1, GT, false>);
         if (lds_bytes > 64 * 1024 - 64) {
-            // opt in to more than the default 64 KB of dynamic LDS (once per instantiation is enough, but the call is cheap)
-            const void* fn = vec4 ? (want_cd ? (const void*)mix_deg_kernel<4, GT, true> : (const void*)mix_deg_kernel<4, GT, false>)
-                                  : (want_cd ? (const void*)mix_deg_kernel<1, GT, true> : (const void*)mix_deg_kernel<1, GT, false>);
+            // opt in to more than the default 64 KB of dynamic LDS
             const hipError_t ea = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDegLdsLimit);
             if (ea != hipSuccess) return hip_fail(ea, "hipFuncSetAttribute(MaxDynamicSharedMemorySize)");
         }
+        int per_cu = resident_per_cu(fn, lds_bytes);
+        if (per_cu > 2 * kGridPerCu) per_cu = 2 * kGridPerCu;
+        const int64_t cap = (int64_t)di->cus * per_cu;
+        grid = (int)(ntiles < cap ? ntiles : cap);
+        const dim3 g(grid), b(kThreads);
         if (vec4 && want_cd)
             hipLaunchKernelGGL((mix_deg_kernel<4, GT, true>), g, b, lds_bytes, s, X, X_out, G, nbr, w, deg, n, d, ld,
                                neg_lr, lpr, partials);
@@ -866,11 +927,10 @@ int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, name);
     if (want_cd) {
-        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, partials, grid, cd_out, 0);
+        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, partials, grid, cd_out);
         e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e, "consensus_final_kernel");
     }
-    if (cd_after) return consensus_enqueue(X_out, ldo, n, d, cd_out, s, 1);
     return PSGD_OK;
 }
 
@@ -899,15 +959,15 @@ int mix_full_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
         return fail(PSGD_EALIAS, "%s: X_out partially overlaps X", name);
     }
     if (rows_overlap(G, bg, grow, X_out, bo, xrow, n)) return fail(PSGD_EALIAS, "%s: X_out overlaps G", name);
-    if (want_cd && (rows_overlap(cd_out, 8, 8, X_out, bo, xrow, n) || rows_overlap(cd_out, 8, 8, X, bx, xrow, n) ||
-                    rows_overlap(cd_out, 8, 8, G, bg, grow, n)))
+    if (want_cd && (scalar_overlaps(cd_out, X_out, bo, xrow, n) || scalar_overlaps(cd_out, X, bx, xrow, n) ||
+                    scalar_overlaps(cd_out, G, bg, grow, n)))
         return fail(PSGD_EALIAS, "%s: the distance output overlaps a data buffer", name);
     hipStream_t s = static_cast<hipStream_t>(stream);
     DeviceInfo* di = nullptr;
     if (d == 0) {
         if (!want_cd) return PSGD_OK;
         if (int rc = device_info(&di, true)) return rc;
-        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, di->scratch, 0, cd_out, 0);
+        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, di->scratch, 0, cd_out);
         const hipError_t e0 = hipGetLastError();
         return e0 == hipSuccess ? PSGD_OK : hip_fail(e0, "consensus_final_kernel");
     }
@@ -930,15 +990,14 @@ int mix_full_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, name);
     if (want_cd) {
-        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, partials, grid, cd_out, 0);
+        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, partials, grid, cd_out);
         e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e, "consensus_final_kernel");
     }
     return PSGD_OK;
 }
 
-int consensus_enqueue(const float* X, int64_t ldx, int n, int64_t d, double* out_dev, hipStream_t s,
-                      int poison_if_flagged) {
+int consensus_enqueue(const float* X, int64_t ldx, int n, int64_t d, double* out_dev, hipStream_t s) {
     DeviceInfo* di = nullptr;
     if (int rc = device_info(&di, true)) return rc;
     const bool vec4 = (d % 4 == 0) && (ldx % 4 == 0) && aligned_to(X, 16);
@@ -950,7 +1009,7 @@ int consensus_enqueue(const float* X, int64_t ldx, int n, int64_t d, double* out
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "consensus_partial_kernel");
     hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, di->scratch, grid,
-                       out_dev ? out_dev : di->scratch + kMaxGrid, poison_if_flagged);
+                       out_dev ? out_dev : di->scratch + kMaxGrid);
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "consensus_final_kernel");
     return PSGD_OK;
@@ -977,7 +1036,7 @@ int consensus_async_impl(const char* name, const float* X, int64_t ldx, int n, i
         // nothing to reduce: the final kernel over zero partials writes 0
         DeviceInfo* di = nullptr;
         if (int rc = device_info(&di, true)) return rc;
-        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, di->scratch, 0, out_dev, 0);
+        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, di->scratch, 0, out_dev);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e, "consensus_final_kernel");
         return PSGD_OK;

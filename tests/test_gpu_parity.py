@@ -367,6 +367,22 @@ def test_degree_k_tables(psgd, n, d, deg, gkind):
     assert np.array_equal(run_step(psgd, X, G, nbr, w, 0.2).view(np.uint32), got.view(np.uint32))
 
 
+@pytest.mark.parametrize("n,deg", [(16, 3), (16, 5), (64, 9), (300, 4)])
+def test_tiled_distance_far_from_origin(psgd, n, deg):
+    """Replicas that agree to 1e-4 but sit at O(1) and move by a common 1000 per step: the tiled
+    path measures against the output of row 0, so the large common shift must cancel exactly
+    (a pivot taken from the inputs would leave only ~4 of the distance's digits)."""
+    d = 4100
+    rng = np.random.default_rng(n + deg)
+    nbr, w = _general_table(n, rng) if deg == 3 else _perm_sum_table(n, deg, rng)
+    X = (np.tile(inp.host_normal_f32((1, d), 1.0, 1), (n, 1)) + inp.host_normal_f32((n, d), 1e-4, 2)).astype(np.float32)
+    G = np.full((n, d), 1000.0, np.float32)
+    got, c = run_step_cd(psgd, X, G, nbr, w, 1.0)
+    assert_close(got, orc.mix_step(X, G, orc.densify(nbr, w), 1.0), rel=REL * max(1.0, deg / 4))
+    c_ref = orc.consensus_dist(got)
+    assert c_ref > 0 and abs(c - c_ref) <= REL * c_ref
+
+
 def test_two_ring_hops_as_one_degree5_table(psgd):
     """A ring that also averages with the second neighbours (5-point stencil, weights 1/5)."""
     n, d = 16, 3000
