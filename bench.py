@@ -29,7 +29,10 @@ HBM_PEAK_GBS = 8000.0
 # chip (factor 2.000), WRITE_SIZE reads them all (factor 1.000).  Workloads not yet measured
 # report null.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg5_n64_d100M_bf16g_randring": (18_750_600 * 2.000 + 25_000_000 * 1.000) * 1024,
+    ("cfg5_n64_d100M_bf16g_randring", "ring"): (18_750_600 * 2.000 + 25_000_000 * 1.000) * 1024,
+    ("cfg5_n64_d100M_bf16g_randring", "degree5"): (18_751_856 * 2.000 + 25_000_067 * 1.000) * 1024,
+    ("cfg5_n64_d100M_bf16g_randring", "degree9"): (18_750_863 * 2.000 + 25_000_033 * 1.000) * 1024,
+    ("cfg5_n64_d100M_bf16g_randring", "full"): (18_750_535 * 2.000 + 25_000_558 * 1.000) * 1024,
 }
 
 
@@ -343,7 +346,8 @@ def main():
                       + (" (with fused consensus statistics)" if fused else ""),
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-            "traffic": None if (args.global_average or deg > 3) else MEASURED_TRAFFIC_BYTES.get(wl.name),
+            "traffic": MEASURED_TRAFFIC_BYTES.get(
+                (wl.name, "full" if args.global_average else "ring" if deg == 3 else "degree%d" % deg)),
             "algorithmic_bytes_per_launch": mix_bytes, "avg_launch_ms": mix_avg,
         },
         "mix_updates_per_s": n * d / (mix_avg * 1e-3),
