@@ -28,9 +28,12 @@ Pins (tests/test_oracle_pins.py, all CPU):
   consensus_dist         closed forms (equal rows -> 0; X[i,j] = i -> d n (n^2-1)/12),
                          contraction bound rho^2 of Eq. 5
   synth_grad / d1d_trajectory   reduce to the undelayed run when the X-dependent term is
-                         zero; the replica mean obeys the two-term linear recurrence.
-                         Beyond those two reductions the delayed trajectory has no
-                         independent closed form: parity unpinned past them.
+                         zero; the replica mean obeys the two-term linear recurrence; on the
+                         fixed ring every eigenmode follows the closed-form solution of
+                         y_{k+1} = lambda y_k - lr c y_{k-1} (characteristic roots); with T_u
+                         the consensus distance is (lr c)^(2 ceil(k/2)) C_0, a noise impulse
+                         returns every second step, and the trajectory is linear in its
+                         inputs; three planted mutants of the delay are caught.
 """
 import numpy as np
 

@@ -439,6 +439,116 @@ def test_d1d_uses_previous_iterate_and_mean_recurrence():
     assert np.allclose([z[0, 0] for z in Z], x, atol=1e-14)
 
 
+def _two_term_closed_form(lam, q, y0, k):
+    """y_k of y_{k+1} = lam y_k - q y_{k-1} with y_{-1} = y_0, from the characteristic roots
+    r^2 - lam r + q = 0 (textbook solution of a linear recurrence; complex roots allowed)."""
+    disc = np.sqrt(complex(lam * lam - 4.0 * q))
+    rp, rm = (lam + disc) / 2.0, (lam - disc) / 2.0
+    # A + B = y0 ;  A / rp + B / rm = y0
+    M = np.array([[1.0, 1.0], [1.0 / rp, 1.0 / rm]])
+    A, B = np.linalg.solve(M, np.array([1.0, 1.0], dtype=complex))
+    return ((A * rp ** k + B * rm ** k) * y0).real
+
+
+def test_d1d_fixed_ring_modes_follow_characteristic_roots():
+    """Noise-free delayed trajectory on the fixed ring: T_0 is symmetric, so in its eigenbasis
+    every mode obeys the scalar recurrence y_{k+1} = lambda_j y_k - lr c y_{k-1} (Eq. 14 with a
+    linear gradient), whose solution is a combination of powers of the two characteristic
+    roots.  Independent of the oracle's step-by-step iteration."""
+    rng = np.random.default_rng(11)
+    n, d, K, lr, c = 8, 5, 14, 0.1, 0.7
+    T = orc.ring_matrix(n)
+    lam, V = np.linalg.eigh(T)
+    X0 = rng.standard_normal((n, d)).astype(np.float32)
+    zeros = [np.zeros((n, d), np.float32)] * K
+    Xs = orc.d1d_trajectory(X0, zeros, [T] * K, lr, c)
+    q = float(np.float32(lr)) * float(np.float32(c))
+    Y0 = V.T @ X0.astype(np.float64)
+    for k in (1, 2, 3, 7, 14):
+        Yk = np.stack([_two_term_closed_form(lam[j], q, Y0[j], k) for j in range(n)])
+        assert np.allclose(Xs[k], V @ Yk, atol=1e-12), k
+    # an undelayed gradient (evaluated at X_k) gives y_k = (lambda - q)^k y_0 instead: the two differ
+    Yk_undelayed = np.stack([(lam[j] - q) ** 7 * Y0[j] for j in range(n)])
+    assert not np.allclose(Xs[7], V @ Yk_undelayed, atol=1e-6)
+
+
+def test_d1d_with_global_averaging_closed_form():
+    """The paper's own delay-by-one (Eq. 13, 14): T_u averages fully, so after one step every
+    disagreement comes from the stale gradient alone: with G = c X_{k-1} and no noise the
+    deviations obey v_{k+1} = -lr c v_{k-1}, hence C_k = (lr c)^(2 ceil(k/2)) C_0, and the mean
+    obeys the two-term recurrence with lambda = 1."""
+    rng = np.random.default_rng(12)
+    n, d, K, lr, c = 6, 7, 9, 0.25, 0.9
+    X0 = rng.standard_normal((n, d)).astype(np.float32)
+    Tu = orc.uniform_matrix(n)
+    Xs = orc.d1d_trajectory(X0, [np.zeros((n, d), np.float32)] * K, [Tu] * K, lr, c)
+    q = float(np.float32(lr)) * float(np.float32(c))
+    C0 = orc.consensus_dist(X0)
+    m0 = X0.astype(np.float64).mean(0)
+    for k in range(1, K + 1):
+        assert np.isclose(orc.consensus_dist(Xs[k]), q ** (2 * ((k + 1) // 2)) * C0, rtol=1e-10, atol=0)
+        assert np.allclose(Xs[k].mean(0), _two_term_closed_form(1.0, q, m0, k), atol=1e-12)
+    # The trajectory is linear in (X_0, noise): response to noise alone, one impulse at step j.
+    # X_{j+1} = -lr e; its deviations then return every second step scaled by -lr c:
+    # C_{j+1+2m} = (lr c)^(2m) lr^2 C(e), and C_{j+2+2m} = 0.
+    j = 2
+    e = rng.standard_normal((n, d)).astype(np.float32)
+    noises = [np.zeros((n, d), np.float32) for _ in range(K)]
+    noises[j] = e
+    Zs = orc.d1d_trajectory(np.zeros((n, d), np.float32), noises, [Tu] * K, lr, c)
+    a = float(np.float32(lr))
+    Ce = orc.consensus_dist(e)
+    for k in range(K + 1):
+        if k <= j:
+            want = 0.0
+        elif (k - j - 1) % 2 == 0:
+            want = q ** (k - j - 1) * a * a * Ce
+        else:
+            want = 0.0
+        assert np.isclose(orc.consensus_dist(Zs[k]), want, rtol=1e-10, atol=1e-24), k
+    both = orc.d1d_trajectory(X0, noises, [Tu] * K, lr, c)
+    for k in range(K + 1):
+        assert np.allclose(both[k], Xs[k] + Zs[k], atol=1e-13)           # superposition
+
+
+def test_d1d_planted_mistakes_are_caught():
+    """Mutants of the delayed driver, planted on the CPU, against the closed form above."""
+    def closed_form_violations(traj):
+        n, d, K, lr, c = 6, 4, 6, 0.25, 0.9
+        X0 = np.random.default_rng(13).standard_normal((n, d)).astype(np.float32)
+        Tu = orc.uniform_matrix(n)
+        Xs = traj(X0, [np.zeros((n, d), np.float32)] * K, [Tu] * K, lr, c)
+        q = float(np.float32(lr)) * float(np.float32(c))
+        C0 = orc.consensus_dist(X0)
+        return sum(not np.isclose(orc.consensus_dist(Xs[k]), q ** (2 * ((k + 1) // 2)) * C0, rtol=1e-10, atol=0)
+                   for k in range(1, K + 1))
+
+    def no_delay(X0, noises, Ts, lr, c):            # gradient at the current iterate
+        Xs = [X0.astype(np.float64)]
+        for k, T in enumerate(Ts):
+            Xs.append(orc.mix_step(Xs[-1], orc.synth_grad(Xs[-1], noises[k], c), T, lr))
+        return Xs
+
+    def two_step_delay(X0, noises, Ts, lr, c):      # gradient two iterates back
+        Xs = [X0.astype(np.float64)]
+        for k, T in enumerate(Ts):
+            Xs.append(orc.mix_step(Xs[-1], orc.synth_grad(Xs[max(k - 2, 0)], noises[k], c), T, lr))
+        return Xs
+
+    def first_step_without_gradient(X0, noises, Ts, lr, c):   # X_{-1} := 0 instead of X_0
+        Xs = [X0.astype(np.float64)]
+        prev = np.zeros_like(Xs[0])
+        for k, T in enumerate(Ts):
+            nxt = orc.mix_step(Xs[-1], orc.synth_grad(prev, noises[k], c), T, lr)
+            prev = Xs[-1]
+            Xs.append(nxt)
+        return Xs
+
+    assert closed_form_violations(orc.d1d_trajectory) == 0
+    for mutant in (no_delay, two_step_delay, first_step_without_gradient):
+        assert closed_form_violations(mutant) > 0, mutant.__name__
+
+
 # ------------------------------------------------------------------ planted mistakes
 def _pins_for_mix(mix):
     """A bundle of the checks above, run against a candidate mix function.  Returns the
