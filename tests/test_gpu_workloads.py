@@ -251,6 +251,35 @@ def test_cfg4_shape_with_global_averaging(psgd):
     torch.cuda.empty_cache()
 
 
+def test_cfg4_shape_noise_free_delay_closed_form(psgd):
+    """Workload 4's shape, global averaging, gradient c X_{k-1} without noise: the deviations
+    obey v_{k+1} = -lr c v_{k-1}, so C_k = (lr c)^(2 ceil(k/2)) C_0 at any size (Sec. 4,
+    Eq. 13 and 14) -- a closed form for the full-size launch, no sampling involved."""
+    wl = inp.workload(4)
+    n, d, lr, c = wl.n, wl.d, 0.1, 0.5
+    bufs = [inp.device_normal_f32((n, d), wl.sigma_x, wl.seed_x) if i == 0 else
+            torch.empty((n, d), device="cuda:0") for i in range(3)]
+    X_prev, X, Y = bufs[1], bufs[0], bufs[2]
+    X_prev.copy_(X)
+    zero = torch.zeros((n, d), device="cuda:0")
+    G = torch.empty((n, d), device="cuda:0")
+    cd = torch.zeros(7, dtype=torch.float64, device="cuda:0")
+    psgd.consensus_dist_async(X, cd[0:1])
+    for k in range(6):
+        psgd.synth_grad(X_prev, zero, G, c)
+        psgd.mix_full(X, Y, G, lr, delay_mode=1, cdist_out=cd[k + 1:k + 2])
+        X_prev, X, Y = X, Y, X_prev
+    torch.cuda.synchronize()
+    got = cd.cpu().numpy()
+    q = float(np.float32(lr)) * float(np.float32(c))
+    assert abs(got[0] / (d * (n - 1) * wl.sigma_x ** 2) - 1) < 8 * math.sqrt(2.0 / d) + 2e-4
+    for k in range(1, 7):
+        want = q ** (2 * ((k + 1) // 2)) * got[0]
+        assert abs(got[k] / want - 1) < 1e-4, (k, got[k], want)
+    del bufs, zero, G
+    torch.cuda.empty_cache()
+
+
 def test_cfg5_bf16_gradients_full_size(psgd):
     """The benchmark's configuration: workload 5 in the row-pitched layout, fused distance."""
     wl = inp.workload(5)
