@@ -357,11 +357,14 @@ __host__ __device__ inline size_t tile_cd_bytes(int lpr, int vec) {
 
 // One output group from the tile: slots in table order, acc = w0 * x0, then one fma per
 // further slot, then the gradient term (for 3 slots this is exactly mix_one's order).
+// 16-bit tables (the degree-K kernel's) hold nbr * lpr, the tile offset of the row, 32-bit ones nbr.
 template <typename V, typename IT>
 __device__ __forceinline__ V mix_slots(const V* tile, const IT* nbr, const float* w, int deg, int lpr, int lane, V g,
                                        float neg_lr) {
-    V acc = tile[nbr[0] * lpr + lane] * w[0];
-    for (int s = 1; s < deg; ++s) acc = vfma(w[s], tile[nbr[s] * lpr + lane], acc);
+    constexpr bool kPremul = sizeof(IT) == 2;
+    const int scale = kPremul ? 1 : lpr;
+    V acc = tile[nbr[0] * scale + lane] * w[0];
+    for (int s = 1; s < deg; ++s) acc = vfma(w[s], tile[nbr[s] * scale + lane], acc);
     return vfma(neg_lr, g, acc);
 }
 
@@ -381,8 +384,10 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
     const Cols<VEC> tag{};
     constexpr int U = kTileUnroll;
     V* tile = reinterpret_cast<V*>(l.scratch);
-    // [4 wavefronts][lpr][VEC] doubles (CD only), 8-byte aligned behind the tile
-    double* comb = reinterpret_cast<double*>((reinterpret_cast<uintptr_t>(tile + (size_t)n * lpr) + 7) & ~(uintptr_t)7);
+    // [4 wavefronts][lpr][VEC] doubles (CD only), 8-byte aligned behind the tile.  The offset is
+    // rounded, not the pointer: a pointer that has been through an integer loses its LDS
+    // address space and every access through it becomes a (slow) generic-address instruction.
+    double* comb = reinterpret_cast<double*>(l.scratch + (((size_t)n * lpr * sizeof(V) + 7) & ~(size_t)7));
     const int lane = threadIdx.x % lpr, rg = threadIdx.x / lpr, nrg = kThreads / lpr;
     const int64_t ntiles = (ncg + lpr - 1) / lpr;
     double total = 0.0;
@@ -527,7 +532,7 @@ __global__ __launch_bounds__(kThreads, 4) void mix_deg_kernel(const float* X, fl
     int ok = 1;
     for (int e = threadIdx.x; e < deg * n; e += kThreads) {
         const int v = nbr[e];
-        l.nbr16[e] = (uint16_t)v;
+        l.nbr16[e] = (uint16_t)(v * lpr);   // tile offset of the row (n * lpr <= 8192 by the tile budget)
         l.w[e] = w[e];
         ok &= (unsigned)v < (unsigned)n;
     }
