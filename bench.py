@@ -96,6 +96,12 @@ def main():
     ap.add_argument("--degree", type=int, default=3,
                     help="odd K > 3: mix with K neighbours on the workload's ring (self and (K-1)/2 learners on each "
                          "side, weight 1/K each) through psgd_mix_step_deg, the general sparse-table kernel")
+    ap.add_argument("--device-tables", action="store_true",
+                    help="build each iteration's table on the device (psgd_build_mixing_device) instead of on the "
+                         "host followed by an upload")
+    ap.add_argument("--graph", action="store_true",
+                    help="after the timed region, capture the same K steps (tables built on the device from a device-side "
+                         "iteration counter) in ONE HIP graph, replay it, and report its time per step beside the eager one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layout", choices=["pitched", "probe", "dense"], default="pitched",
                     help="where the arrays live in HBM: 'pitched' interleaves the rows of all arrays across most of "
@@ -107,8 +113,11 @@ def main():
                     help="before the warm-up, run a plain dense device copy of known size (printed); under "
                          "rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE readings calibrate the mix kernel's")
     args = ap.parse_args()
-    if args.degree < 3 or args.degree % 2 == 0 or (args.degree > 3 and args.global_average):
-        log("bench.py: --degree takes an odd K >= 3 and excludes --global-average")
+    if args.degree < 3 or args.degree % 2 == 0 or (args.degree > 3 and (args.global_average or args.device_tables)):
+        log("bench.py: --degree takes an odd K >= 3 and excludes --global-average and --device-tables")
+        sys.exit(2)
+    if args.graph and (args.degree > 3 or args.overlap):
+        log("bench.py: --graph excludes --degree and --overlap")
         sys.exit(2)
     if args.gpus != 1:
         log("bench.py: this build runs all learners on ONE GPU (no collectives); --gpus %d is not "
@@ -229,13 +238,16 @@ def main():
 
     def one_step(k):
         nonlocal X, Y, X_prev
-        nbr, w = psgd.build_mixing(wl.topology, n, wl.seed_perm, k)
-        if deg > 3:
-            nbr, w = widen(nbr)
-        nbr_host[k].copy_(torch.from_numpy(nbr))
-        w_host[k].copy_(torch.from_numpy(w))
-        nbr_dev[k].copy_(nbr_host[k], non_blocking=True)
-        w_dev[k].copy_(w_host[k], non_blocking=True)
+        if args.device_tables:
+            psgd.build_mixing_device(wl.topology, n, wl.seed_perm, nbr_dev[k], w_dev[k], step_offset=k, stream=stream)
+        else:
+            nbr, w = psgd.build_mixing(wl.topology, n, wl.seed_perm, k)
+            if deg > 3:
+                nbr, w = widen(nbr)
+            nbr_host[k].copy_(torch.from_numpy(nbr))
+            w_host[k].copy_(torch.from_numpy(w))
+            nbr_dev[k].copy_(nbr_host[k], non_blocking=True)
+            w_dev[k].copy_(w_host[k], non_blocking=True)
         G = Gs[k % 2]
         overlap = wl.delay and args.overlap
         if overlap:
@@ -290,6 +302,48 @@ def main():
             one_step(k)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
+    graph_report = None
+    if args.graph:
+        # The same K steps as one graph: {table from the device-side counter, counter += 1, fused step} x K.
+        step_dev = torch.full((1,), total, dtype=torch.int64, device=dev)
+        tab_n = torch.empty((n, 3), dtype=torch.int32, device=dev)
+        tab_w = torch.empty((n, 3), dtype=torch.float32, device=dev)
+
+        def graph_step(k, cur):
+            nonlocal X, Y, X_prev
+            psgd.build_mixing_device(wl.topology, n, wl.seed_perm, tab_n, tab_w, step_dev=step_dev, advance=1, stream=cur)
+            G = Gs[k % 2]
+            if wl.delay:
+                psgd.synth_grad(X_prev, noise, G, wl.grad_pull, stream=cur)
+            cd = None if args.no_consensus else cdist[k:k + 1]
+            if args.global_average:
+                psgd.mix_full(X, Y, G, wl.lr, delay_mode=1 if wl.delay else 0, stream=cur,
+                              cdist_out=None if args.unfused else cd)
+            else:
+                psgd.mix_step(X, Y, G, tab_n, tab_w, wl.lr, delay_mode=1 if wl.delay else 0, stream=cur,
+                              cdist_out=None if args.unfused else cd)
+            if args.unfused and cd is not None:
+                psgd.consensus_dist_async(Y, cd, stream=cur)
+            if wl.delay:
+                X_prev, X, Y = X, Y, X_prev
+            elif not args.in_place:
+                X, Y = Y, X
+
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr, stream=stream):
+            for k in range(K):
+                graph_step(k, torch.cuda.current_stream())
+        gr.replay()                                  # warm-up replay
+        torch.cuda.synchronize()
+        reps = 3
+        tg0 = time.perf_counter()
+        for _ in range(reps):
+            gr.replay()
+        torch.cuda.synchronize()
+        tg1 = time.perf_counter()
+        gms = 1e3 * (tg1 - tg0) / (reps * K)
+        graph_report = {"steps_per_graph": K, "replays": reps, "ms_per_step": gms, "value": n * d / (gms * 1e-3)}
+        log("HIP graph of %d steps: %.4f ms per step over %d replays" % (K, gms, reps))
     if psgd.device_status() != 0:
         log("bench.py: a kernel flagged an invalid mixing table")
         sys.exit(4)
@@ -333,7 +387,7 @@ def main():
         "config": {
             "workload": wl.name, "n": n, "d": d, "g_dtype": wl.g_dtype,
             "topology": "full (T_u)" if args.global_average else {0: "ring", 1: "rand_ring"}[wl.topology],
-            "table_degree": deg,
+            "table_degree": deg, "tables_built_on": "device" if args.device_tables else "host",
             "lr": wl.lr,
             "delay_by_one": wl.delay, "consensus_every_step": not args.no_consensus,
             "consensus_fused_into_mix_kernel": fused,
@@ -352,6 +406,8 @@ def main():
         },
         "mix_updates_per_s": n * d / (mix_avg * 1e-3),
     }
+    if graph_report is not None:
+        result["hip_graph"] = graph_report
     if not (args.no_consensus or fused):
         result["consensus"] = {"avg_ms": con_avg, "achieved_GBps": 4 * n * d / (con_avg * 1e-3) / 1e9,
                                "frac": 4 * n * d / (con_avg * 1e-3) / 1e9 / HBM_PEAK_GBS}

@@ -74,6 +74,25 @@ int psgd_build_mixing(int topology, int n, uint64_t seed, uint64_t step,
                       int32_t* nbr, float* w);
 
 /*
+ * psgd_build_mixing_device - the same table, built on the device by work enqueued on `stream`.
+ * The shared-seed rule of Sec. 4 makes the ring of an iteration a function of (n, seed, step)
+ * alone, so no host needs to take part: the iteration number itself may live in device memory.
+ *
+ *   step_dev     device, uint64 (8-byte aligned), or NULL.  The table is that of iteration
+ *                step = (step_dev ? *step_dev : 0) + step_offset  (mod 2^64).
+ *   advance      if step_dev is not NULL, *step_dev += advance after it has been read (0 leaves it).
+ *   nbr, w       device, int32 / float [n * 3], written; layout and values bit-identical to
+ *                psgd_build_mixing(topology, n, seed, step, ...).
+ *
+ * A captured HIP graph that holds this call with advance = 1 followed by a step call therefore
+ * runs iteration k, k+1, ... on successive replays without any host work or upload.
+ * Asynchronous.  Errors: as psgd_build_mixing, plus PSGD_EALIGN, PSGD_EALIAS (nbr, w and
+ * step_dev overlap) and PSGD_EHIP.
+ */
+int psgd_build_mixing_device(int topology, int n, uint64_t seed, uint64_t* step_dev, uint64_t step_offset,
+                             int advance, int32_t* nbr, float* w, void* stream);
+
+/*
  * psgd_mix_step - fused model averaging and SGD step (Sec. 2, Eq. 2), gradients in fp32.
  *
  *   X      device, float [n * d] row-major, read

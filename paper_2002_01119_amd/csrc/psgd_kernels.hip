@@ -712,6 +712,57 @@ __global__ __launch_bounds__(kThreads) void synth_grad_rows_kernel(const float* 
 }
 
 // ---------------------------------------------------------------------------------------
+// Mixing table of one iteration, built on the device (Sec. 4: all learners derive the same
+// ring from a shared seed, so the table is a function of (n, seed, step) only).  One
+// workgroup: the SplitMix64 draws are counter-based (state of draw t = state0 + (t + 1) *
+// increment), so all swap partners are computed in parallel; only the n - 1 swaps of the
+// Durstenfeld shuffle are serial (one lane, in LDS).
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void build_mixing_kernel(int randomize, int n, uint64_t seed,
+                                                                uint64_t* step_dev, uint64_t step_offset,
+                                                                uint64_t advance, int32_t* __restrict__ nbr,
+                                                                float* __restrict__ w) {
+    __shared__ int sigma[PSGD_MAX_N];
+    __shared__ int partner[PSGD_MAX_N];
+    const int tid = threadIdx.x;
+    const uint64_t base = step_dev ? *static_cast<volatile uint64_t*>(step_dev) : 0ull;
+    const uint64_t step = base + step_offset;
+    for (int p = tid; p < n; p += kThreads) sigma[p] = p;
+    if (randomize) {
+        constexpr uint64_t kWeyl = 0x9E3779B97F4A7C15ull;
+        const uint64_t state0 = seed ^ ((step + 1ull) * kWeyl);
+        for (int t = tid; t < n - 1; t += kThreads) {
+            const int i = n - 1 - t;                      // draw t serves position i
+            uint64_t z = state0 + (uint64_t)(t + 1) * kWeyl;
+            z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+            z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+            z ^= z >> 31;
+            partner[i] = (int)__umul64hi(z, (uint64_t)(i + 1));
+        }
+        __syncthreads();
+        if (tid == 0) {
+            for (int i = n - 1; i >= 1; --i) {
+                const int j = partner[i], t = sigma[i];
+                sigma[i] = sigma[j];
+                sigma[j] = t;
+            }
+        }
+    }
+    __syncthreads();
+    const float third = 1.0f / 3.0f;
+    for (int p = tid; p < n; p += kThreads) {
+        const int me = sigma[p];
+        nbr[3 * me + 0] = me;
+        nbr[3 * me + 1] = sigma[p == 0 ? n - 1 : p - 1];
+        nbr[3 * me + 2] = sigma[p == n - 1 ? 0 : p + 1];
+        w[3 * me + 0] = third;
+        w[3 * me + 1] = third;
+        w[3 * me + 2] = third;
+    }
+    if (tid == 0 && step_dev && advance) *step_dev = base + advance;
+}
+
+// ---------------------------------------------------------------------------------------
 // Host helpers.
 // ---------------------------------------------------------------------------------------
 struct DeviceInfo {
@@ -1119,6 +1170,30 @@ int psgd_mix_full(const float* X, int64_t ldx, float* X_out, int64_t ldo, const 
                                              n, d, lr, delay_mode, cdist_out, stream);
     return psgd::mix_full_impl<float>("psgd_mix_full", X, ldx, X_out, ldo, static_cast<const float*>(G), ldg, n, d, lr,
                                       delay_mode, cdist_out, stream);
+}
+
+int psgd_build_mixing_device(int topology, int n, uint64_t seed, uint64_t* step_dev, uint64_t step_offset, int advance,
+                             int32_t* nbr, float* w, void* stream) {
+    using namespace psgd;
+    clear_error();
+    if (!nbr || !w) return fail(PSGD_EINVAL, "psgd_build_mixing_device: null output pointer");
+    if (n < 1 || n > PSGD_MAX_N)
+        return fail(PSGD_EINVAL, "psgd_build_mixing_device: n=%d outside 1..%d", n, (int)PSGD_MAX_N);
+    if (topology == PSGD_TOPO_FULL)
+        return fail(PSGD_EINVAL, "psgd_build_mixing_device: the uniform topology has no 3-slot table, use psgd_mix_full");
+    if (topology != PSGD_TOPO_RING && topology != PSGD_TOPO_RAND_RING)
+        return fail(PSGD_EINVAL, "psgd_build_mixing_device: unknown topology %d", topology);
+    if (advance < 0) return fail(PSGD_EINVAL, "psgd_build_mixing_device: advance=%d is negative", advance);
+    if (!aligned_to(nbr, 4) || !aligned_to(w, 4) || (step_dev && !aligned_to(step_dev, 8)))
+        return fail(PSGD_EALIGN, "psgd_build_mixing_device: pointer not aligned to its element size");
+    const size_t tb = (size_t)n * 3 * 4;
+    if (overlaps(nbr, tb, w, tb) || (step_dev && (overlaps(step_dev, 8, nbr, tb) || overlaps(step_dev, 8, w, tb))))
+        return fail(PSGD_EALIAS, "psgd_build_mixing_device: nbr, w and step_dev overlap");
+    hipLaunchKernelGGL(build_mixing_kernel, dim3(1), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
+                       topology == PSGD_TOPO_RAND_RING ? 1 : 0, n, seed, step_dev, step_offset, (uint64_t)advance, nbr, w);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "build_mixing_kernel");
+    return PSGD_OK;
 }
 
 double psgd_consensus_dist(const float* X, int n, int64_t d) {

@@ -22,7 +22,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libpsgd.so
 _lib = None
 
 EXPORTS = (
-    "psgd_build_mixing", "psgd_mix_step", "psgd_mix_step_bf16g", "psgd_mix_step_cd",
+    "psgd_build_mixing", "psgd_build_mixing_device", "psgd_mix_step", "psgd_mix_step_bf16g", "psgd_mix_step_cd",
     "psgd_mix_step_cd_bf16g", "psgd_mix_step_ex", "psgd_mix_step_deg", "psgd_mix_full", "psgd_consensus_dist", "psgd_consensus_dist_ex",
     "psgd_consensus_dist_async", "psgd_synth_grad", "psgd_synth_grad_ex", "psgd_device_status", "psgd_last_error",
     "psgd_version",
@@ -50,6 +50,9 @@ def load(reload=False):
     lib.psgd_build_mixing.restype = ctypes.c_int
     lib.psgd_build_mixing.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint64,
                                       c_i32p, c_f32p]
+    lib.psgd_build_mixing_device.restype = ctypes.c_int
+    lib.psgd_build_mixing_device.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_uint64, vp, ctypes.c_uint64,
+                                             ctypes.c_int, vp, vp, vp]
     for name in ("psgd_mix_step", "psgd_mix_step_bf16g"):
         fn = getattr(lib, name)
         fn.restype = ctypes.c_int
@@ -130,6 +133,24 @@ def build_mixing(topology, n, seed=0, step=0):
         int(topology), int(n), ctypes.c_uint64(seed & (2 ** 64 - 1)), ctypes.c_uint64(step & (2 ** 64 - 1)),
         nbr.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), w.ctypes.data_as(ctypes.POINTER(ctypes.c_float))))
     return nbr, w
+
+
+def build_mixing_device(topology, n, seed, nbr, w, step_dev=None, step_offset=0, advance=0, stream=None):
+    """Enqueue the construction of the same table in device memory: nbr int32 [n,3], w float32
+    [n,3] (device tensors, written).  The iteration is step_offset plus, if given, the value of
+    step_dev (device int64 / uint64 tensor, >= 1 element), which is then advanced by `advance`."""
+    import torch
+    if nbr.dtype != torch.int32 or w.dtype != torch.float32 or nbr.numel() != 3 * n or w.numel() != 3 * n \
+            or not nbr.is_contiguous() or not w.is_contiguous():
+        raise ValueError("nbr must be int32 [n,3] and w float32 [n,3], contiguous")
+    sp = None
+    if step_dev is not None:
+        if step_dev.dtype not in (torch.int64, torch.uint64) or step_dev.numel() < 1 or step_dev.device != nbr.device:
+            raise ValueError("step_dev must be a 64-bit integer device tensor")
+        sp = step_dev.data_ptr()
+    _check(load().psgd_build_mixing_device(
+        int(topology), int(n), ctypes.c_uint64(seed & (2 ** 64 - 1)), sp, ctypes.c_uint64(step_offset & (2 ** 64 - 1)),
+        int(advance), nbr.data_ptr(), w.data_ptr(), _stream_handle(stream)))
 
 
 def mix_step(X, X_out, G, nbr, w, lr, delay_mode=0, stream=None, cdist_out=None):

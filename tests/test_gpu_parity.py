@@ -673,3 +673,70 @@ def test_steps_captured_in_a_hip_graph_replay_exactly(psgd):
         assert torch.equal(c_graph, c_eager), rep
         # eager work of the same library between replays
         assert abs(psgd.consensus_dist(out) - c_eager[-1].item()) <= 1e-9 * c_eager[-1].item()
+
+
+# ------------------------------------------------------------------------- tables built on the device
+@pytest.mark.parametrize("n", [1, 2, 3, 5, 8, 64, 128, 257, 512])
+def test_device_built_tables_bit_identical_to_oracle(psgd, n):
+    nbr = torch.full((n, 3), -7, dtype=torch.int32, device="cuda:0")
+    w = torch.full((n, 3), float("nan"), device="cuda:0")
+    for topo in (psgd.TOPO_RING, psgd.TOPO_RAND_RING):
+        for seed, step in ((0, 0), (1, 7), (3005, 19), (2 ** 63 + 5, 2 ** 40 + 3), (2 ** 64 - 1, 2 ** 64 - 1)):
+            psgd.build_mixing_device(topo, n, seed, nbr, w, step_offset=step)
+            onbr, ow = orc.neighbour_table(topo, n, seed, step)
+            assert np.array_equal(nbr.cpu().numpy(), onbr), (topo, n, seed, step)
+            assert np.array_equal(w.cpu().numpy().view(np.uint32), ow.view(np.uint32))
+
+
+def test_device_step_counter_advances(psgd):
+    n, seed = 33, 77
+    nbr = torch.empty((n, 3), dtype=torch.int32, device="cuda:0")
+    w = torch.empty((n, 3), device="cuda:0")
+    step = torch.tensor([5], dtype=torch.int64, device="cuda:0")
+    for k in range(4):
+        psgd.build_mixing_device(psgd.TOPO_RAND_RING, n, seed, nbr, w, step_dev=step, step_offset=100, advance=2)
+        assert np.array_equal(nbr.cpu().numpy(), orc.neighbour_table(orc.TOPO_RAND_RING, n, seed, 105 + 2 * k)[0])
+        assert step.item() == 5 + 2 * (k + 1)
+    psgd.build_mixing_device(psgd.TOPO_RAND_RING, n, seed, nbr, w, step_dev=step)      # advance = 0: read only
+    assert step.item() == 13
+    assert np.array_equal(nbr.cpu().numpy(), orc.neighbour_table(orc.TOPO_RAND_RING, n, seed, 13)[0])
+
+
+def test_graph_of_table_build_and_step_walks_the_iterations(psgd):
+    """One captured graph = {build the iteration's ring from the device-side counter, advance the
+    counter, mix in place}.  Each replay must be the next iteration of the randomized-ring
+    run: compared with the oracle's trajectory, with eager work between replays."""
+    n, d, seed, lr, steps = 16, 12_004, 41, 0.05, 5
+    X0 = inp.host_normal_f32((n, d), 1.0, 51)
+    Gh = inp.host_normal_f32((n, d), 0.1, 52)
+    X, G = dev(X0), dev(Gh)
+    nbr = torch.empty((n, 3), dtype=torch.int32, device="cuda:0")
+    w = torch.empty((n, 3), device="cuda:0")
+    step = torch.zeros(1, dtype=torch.int64, device="cuda:0")
+    c = torch.zeros(1, dtype=torch.float64, device="cuda:0")
+    scratch = torch.empty_like(X)
+    psgd.mix_step(X, scratch, G, dev(psgd.build_mixing(psgd.TOPO_RING, n)[0]),
+                  dev(psgd.build_mixing(psgd.TOPO_RING, n)[1]), lr, cdist_out=c)     # library scratch exists before capture
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        cur = torch.cuda.current_stream()
+        psgd.build_mixing_device(psgd.TOPO_RAND_RING, n, seed, nbr, w, step_dev=step, advance=1, stream=cur)
+        psgd.mix_step(X, X, G, nbr, w, lr, cdist_out=c, stream=cur)
+    X.copy_(dev(X0))
+    step.zero_()
+    torch.cuda.synchronize()
+    Xo = X0.astype(np.float64)
+    for k in range(steps):
+        g.replay()
+        torch.cuda.synchronize()
+        T = orc.mixing_matrix(orc.TOPO_RAND_RING, n, seed, k)
+        Xo = orc.mix_step(Xo, Gh, T, lr)
+        got = X.cpu().numpy()
+        assert_close(got, Xo, rel=REL * (k + 1))
+        assert step.item() == k + 1
+        assert np.array_equal(nbr.cpu().numpy(), orc.neighbour_table(orc.TOPO_RAND_RING, n, seed, k)[0])
+        c_ref = orc.consensus_dist(got)
+        assert abs(c.item() - c_ref) <= REL * c_ref
+        assert abs(psgd.consensus_dist(X) - c_ref) <= REL * c_ref          # eager work between replays

@@ -77,6 +77,24 @@ def test_build_mixing_rejects_bad_arguments():
         psgd.build_mixing(psgd.TOPO_RING, 0)
 
 
+def test_build_mixing_device_argument_checks():
+    lib = psgd.load()
+    A, B, S = 0x100000, 0x200000, 0x300000
+    fn = lib.psgd_build_mixing_device
+    assert fn(0, 0, 0, None, 0, 0, A, B, None) == psgd.EINVAL
+    assert fn(0, psgd.MAX_N + 1, 0, None, 0, 0, A, B, None) == psgd.EINVAL
+    assert fn(5, 4, 0, None, 0, 0, A, B, None) == psgd.EINVAL and "topology" in psgd.last_error()
+    assert fn(psgd.TOPO_FULL, 4, 0, None, 0, 0, A, B, None) == psgd.EINVAL
+    assert fn(1, 4, 0, None, 0, 0, None, B, None) == psgd.EINVAL
+    assert fn(1, 4, 0, None, 0, 0, A, None, None) == psgd.EINVAL
+    assert fn(1, 4, 0, S, 0, -1, A, B, None) == psgd.EINVAL and "advance" in psgd.last_error()
+    assert fn(1, 4, 0, S + 4, 0, 0, A, B, None) == psgd.EALIGN
+    assert fn(1, 4, 0, None, 0, 0, A + 2, B, None) == psgd.EALIGN
+    assert fn(1, 4, 0, None, 0, 0, A, A + 16, None) == psgd.EALIAS
+    assert fn(1, 4, 0, A + 8, 0, 1, A, B, None) == psgd.EALIAS
+    assert fn(1, 4, 0, S, 0, 1, A, B, None) in (psgd.OK, psgd.EHIP)      # valid: only a device is missing here
+
+
 def test_mix_step_argument_checks_need_no_device():
     """Validation runs before any HIP call, so fake (never dereferenced) addresses do."""
     lib = psgd.load()
