@@ -1,0 +1,49 @@
+"""The benchmark's command-line contract: one JSON line with the agreed keys; more than one
+GPU is refused with a message (this build has no collectives)."""
+import json
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_more_than_one_gpu_is_refused():
+    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert p.returncode == 2
+    assert "ONE GPU" in p.stderr and p.stdout.strip() == ""
+
+
+def test_bad_degree_is_refused():
+    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--degree", "4"], capture_output=True,
+                       text=True, timeout=120)
+    assert p.returncode == 2 and "--degree" in p.stderr
+
+
+@pytest.mark.gpu
+def test_json_line_on_the_small_workload():
+    torch = pytest.importorskip("torch")
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", "1", "--steps", "4", "--warmup", "1",
+                        "--graph"], capture_output=True, text=True, timeout=600)
+    assert p.returncode == 0, p.stderr[-2000:]
+    lines = [l for l in p.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    r = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert key in r, key
+    assert r["n_gpus"] == 1 and r["steps"] == 4 and r["warmup"] == 1 and r["unit"] == "updates/s"
+    assert r["config"]["workload"].startswith("cfg1") and r["vs_baseline"] is None and r["data"] == "synthetic"
+    roof = r["roofline"]
+    assert roof["bound"] == "hbm" and roof["peak"] == 8000.0 and roof["unit"] == "GB/s"
+    assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-12 and 0 < roof["frac"] < 1
+    assert roof["algorithmic_bytes_per_launch"] == 12 * 8 * 1_000_000
+    cb = r["cpu_baseline"]
+    assert cb["kind"] == "oracle" and cb["value"] > 0 and cb["cores"] >= 1 and cb["sample"]
+    assert abs(r["value"] - 8 * 1_000_000 * 4 / (r["ms_per_step"] * 4e-3)) <= 1e-6 * r["value"]
+    assert r["hip_graph"]["ms_per_step"] > 0
