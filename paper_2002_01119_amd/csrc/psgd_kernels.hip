@@ -820,6 +820,18 @@ bool rows_overlap(const void* A, int64_t lda, size_t ra, const void* B, int64_t 
     const size_t span_a = (size_t)(n - 1) * (size_t)lda + ra, span_b = (size_t)(n - 1) * (size_t)ldb + rb;
     if (!overlaps(A, span_a, B, span_b)) return false;
     if ((size_t)lda == ra && (size_t)ldb == rb) return true;  // both dense: the spans are the arrays
+    if (lda == ldb) {
+        // Equal pitches P: row i of A meets row j of B iff  D - ra < (i - j) P < D + rb  with D = B - A.
+        // Take the largest k = i - j (|k| <= n - 1) below the upper bound; smaller k only move away
+        // from the lower one.
+        const int64_t P = lda;
+        const int64_t D = (int64_t)(reinterpret_cast<uintptr_t>(B) - reinterpret_cast<uintptr_t>(A));
+        const int64_t t = D + (int64_t)rb - 1;
+        int64_t k = t >= 0 ? t / P : -((-t + P - 1) / P);       // floor(t / P)
+        if (k > n - 1) k = n - 1;
+        if (k < -(int64_t)(n - 1)) return false;
+        return k * P > D - (int64_t)ra;
+    }
     const uintptr_t a0 = reinterpret_cast<uintptr_t>(A), b0 = reinterpret_cast<uintptr_t>(B);
     for (int i = 0; i < n; ++i) {
         const uintptr_t ai = a0 + (uintptr_t)i * (uintptr_t)lda;

@@ -184,3 +184,32 @@ def test_no_device_is_reported_not_crashed():
     lib = psgd.load()
     rc = lib.psgd_mix_step(0x100000, 0x900000, 0x1100000, 0x2000000, 0x2001000, 4, 1000, 0.1, 0, None)
     assert rc == psgd.EHIP and psgd.last_error() != ""
+
+
+def test_pitched_overlap_verdict_matches_brute_force():
+    """The alias check of the row-pitched entry points against a plain double loop over all row
+    pairs, on random interleavings (fake addresses: the verdict is reached before any device call)."""
+    lib = psgd.load()
+    rng = np.random.default_rng(3)
+    T1, T2 = 0x7000000000, 0x7000001000
+    G = 0x6000000000              # gradients far away from both
+    hits = 0
+    for _ in range(400):
+        n = int(rng.integers(1, 9))
+        d = int(rng.integers(1, 40))
+        P = d + int(rng.integers(0, 60))                  # pitch in elements
+        a0 = 0x1000000 + 4 * int(rng.integers(0, 50))
+        b0 = a0 + 4 * int(rng.integers(-3 * P, 3 * P + 1))
+        if b0 == a0:
+            continue                                       # exact aliasing is the in-place case
+        same = bool(rng.integers(0, 2))
+        Pb = P if same else d + int(rng.integers(0, 60))
+        brute = False
+        for i in range(n):
+            for j in range(n):
+                ai, bj = a0 + 4 * i * (P if n > 1 else d), b0 + 4 * j * (Pb if n > 1 else d)
+                brute |= ai < bj + 4 * d and bj < ai + 4 * d
+        rc = lib.psgd_mix_step_ex(a0, P, b0, Pb, G, d, 0, T1, T2, n, d, 0.1, 0, None, None)
+        assert (rc == psgd.EALIAS) == brute, (n, d, P, Pb, a0, b0, rc, brute)
+        hits += brute
+    assert 50 < hits < 350
