@@ -368,6 +368,8 @@ __device__ __forceinline__ V mix_slots(const V* tile, const IT* nbr, const float
     return vfma(neg_lr, g, acc);
 }
 
+// FULL states that every lane owns a whole number of batches (n is a multiple of kTileUnroll row
+// groups), which removes the per-row guards.
 // A lane's rows are rg, rg + nrg, ...; they are handled kTileUnroll at a time: that many loads
 // are in flight together, and the table look-ups and tile reads of that many rows (independent
 // chains of two dependent LDS reads per slot) interleave instead of queueing behind each other.
@@ -377,7 +379,7 @@ __device__ __forceinline__ V mix_slots(const V* tile, const IT* nbr, const float
 // of row 0, which every row group computes for itself (bit-identical: same tile, same table,
 // same gradient bits; the extra read of G's row 0 is served by the cache).  The squares then
 // add up lane by lane and only the plain sums need merging per column, through LDS.
-template <int VEC, typename GT, bool CD, typename IT>
+template <int VEC, typename GT, bool CD, typename IT, bool FULL = false>
 __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ G, const Lds& l, const IT* nbr_tab,
                             int n, Pitch ld, int64_t ncg, float neg_lr, int lpr, double inv_n, int deg = 3) {
     typedef typename Cols<VEC>::T V;
@@ -403,19 +405,19 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int r = rg + u * nrg;
-                if (r < n) gs[u] = ld_g(G + (int64_t)r * ld.g + col, tag);
+                if (FULL || r < n) gs[u] = ld_g(G + (int64_t)r * ld.g + col, tag);
             }
-            for (int r0 = rg; r0 < n; r0 += kTileUnroll * nrg) {
-                V xs[kTileUnroll];
+            for (int r0 = rg; r0 < n; r0 += U * nrg) {
+                V xs[U];
 #pragma unroll
-                for (int u = 0; u < kTileUnroll; ++u) {
+                for (int u = 0; u < U; ++u) {
                     const int r = r0 + u * nrg;
-                    if (r < n) xs[u] = ld_x(X + (int64_t)r * ld.x + col, tag);
+                    if (FULL || r < n) xs[u] = ld_x(X + (int64_t)r * ld.x + col, tag);
                 }
 #pragma unroll
-                for (int u = 0; u < kTileUnroll; ++u) {
+                for (int u = 0; u < U; ++u) {
                     const int r = r0 + u * nrg;
-                    if (r < n) tile[r * lpr + lane] = xs[u];
+                    if (FULL || r < n) tile[r * lpr + lane] = xs[u];
                 }
             }
         }
@@ -430,13 +432,13 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
                         const int r = r0 + u * nrg;
-                        if (r < n) gs[u] = ld_g(G + (int64_t)r * ld.g + col, tag);
+                        if (FULL || r < n) gs[u] = ld_g(G + (int64_t)r * ld.g + col, tag);
                     }
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int r = r0 + u * nrg;
-                    if (r < n) {
+                    if (FULL || r < n) {
                         const V out = mix_slots<V>(tile, nbr_tab + deg * r, l.w + deg * r, deg, lpr, lane, gs[u], neg_lr);
                         st_x(Xout + (int64_t)r * ld.o + col, out);
                         if (CD) {
@@ -541,7 +543,13 @@ __global__ __launch_bounds__(kThreads, 4) void mix_deg_kernel(const float* X, fl
         if (CD && threadIdx.x == 0) partials[blockIdx.x] = __builtin_nan("");
         return;
     }
-    const double total = tile_path<VEC, GT, CD>(X, Xout, G, l, l.nbr16, n, ld, d / VEC, neg_lr, lpr, 1.0 / (double)n, deg);
+    const int nrg = kThreads / lpr;
+    const double inv_n = 1.0 / (double)n;
+    double total;
+    if (n % (kTileUnroll * nrg) == 0)
+        total = tile_path<VEC, GT, CD, uint16_t, true>(X, Xout, G, l, l.nbr16, n, ld, d / VEC, neg_lr, lpr, inv_n, deg);
+    else
+        total = tile_path<VEC, GT, CD, uint16_t, false>(X, Xout, G, l, l.nbr16, n, ld, d / VEC, neg_lr, lpr, inv_n, deg);
     if (CD) {
         const double bs = block_sum(total, lds4);
         if (threadIdx.x == 0) partials[blockIdx.x] = bs;
