@@ -371,8 +371,9 @@ def main():
     log("whole step: %.3f ms wall per step over %d steps" % (1e3 * wall / K, K))
 
     result = {
-        "metric": "replica-param updates/s for the fused mix+SGD step (whole hot-path step: table build, "
-                  "mix+SGD kernel, consensus distance)",
+        "metric": "replica-param updates/s and achieved HBM GB/s (% of peak) for fused mix+SGD step",
+        "metric_note": "value = replica-parameter updates per second of the whole hot-path step (table build, fused "
+                       "mix+SGD kernel, consensus distance); achieved HBM GB/s and its fraction of the peak are in roofline",
         "value": n * d * K / wall,
         "unit": "updates/s",
         "n_gpus": 1,
