@@ -47,3 +47,25 @@ def test_json_line_on_the_small_workload():
     assert cb["kind"] == "oracle" and cb["value"] > 0 and cb["cores"] >= 1 and cb["sample"]
     assert abs(r["value"] - 8 * 1_000_000 * 4 / (r["ms_per_step"] * 4e-3)) <= 1e-6 * r["value"]
     assert r["hip_graph"]["ms_per_step"] > 0
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("flags", [
+    ["--workload", "2", "--layout", "dense", "--unfused"],
+    ["--workload", "2", "--layout", "probe", "--in-place"],
+    ["--workload", "2", "--global-average", "--device-tables"],
+    ["--workload", "2", "--degree", "5"],
+    ["--workload", "4", "--overlap"],
+    ["--workload", "4", "--graph", "--no-consensus"],
+])
+def test_variants_run_and_report(flags):
+    """Every benchmark variant runs to completion and prints one well-formed line."""
+    torch = pytest.importorskip("torch")
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--steps", "3", "--warmup", "1",
+                        "--no-cpu-baseline"] + flags, capture_output=True, text=True, timeout=600)
+    assert p.returncode == 0, p.stderr[-2000:]
+    r = json.loads(p.stdout.strip())
+    assert r["value"] > 1e10 and 0.2 < r["roofline"]["frac"] < 1.0, r
+    assert r["config"]["workload"].startswith("cfg" + flags[1])
