@@ -1,0 +1,88 @@
+"""Seeded sweep of random VALID shapes, tables and layouts against the oracle: every case draws
+n, d, the table kind (fixed ring, random ring, general 3-slot, degree-K), the gradient type,
+dense or pitched rows (aligned or not), in place or not, with or without the fused distance."""
+import numpy as np
+import pytest
+
+from oracle import psgd_oracle as orc
+from paper_2002_01119_amd import inputs as inp
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+REL = 1e-6
+
+
+@pytest.fixture(scope="module")
+def psgd():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2002_01119_amd import psgd as m
+    m.load()
+    torch.cuda.set_device(0)
+    return m
+
+
+def _table(psgd, rng, n):
+    kind = rng.choice(["ring", "rand", "general3", "deg"])
+    if kind == "ring":
+        return psgd.build_mixing(psgd.TOPO_RING, n) + (4,)
+    if kind == "rand":
+        return psgd.build_mixing(psgd.TOPO_RAND_RING, n, int(rng.integers(0, 2 ** 62)), int(rng.integers(0, 1000))) + (4,)
+    deg = 3 if kind == "general3" else int(rng.integers(1, min(32, 4096 // n) + 1))
+    c = rng.random(deg).astype(np.float32) + np.float32(0.05)
+    c /= c.sum()
+    nbr = np.stack([rng.permutation(n) for _ in range(deg)], axis=1).astype(np.int32)
+    w = np.tile(c, (n, 1)).astype(np.float32)
+    return nbr, w, deg + 1
+
+
+@pytest.mark.parametrize("block", range(12))
+def test_random_cases(psgd, block):
+    rng = np.random.default_rng(1000 + block)
+    for case in range(40):
+        n = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 16, 17, 32, 33, 64, 100, 128, 200, 512]))
+        d = int(rng.choice([1, 3, 4, 8, 60, 255, 256, 1000, 1028, 4096, 5001, 20_000]))
+        if n * d > 3_000_000:
+            d = max(1, 3_000_000 // n)
+        nbr, w, roundings = _table(psgd, rng, n)
+        bf16 = bool(rng.integers(0, 2))
+        pitched = bool(rng.integers(0, 2))
+        in_place = bool(rng.integers(0, 2))
+        want_cd = bool(rng.integers(0, 2))
+        lr = float(rng.choice([0.0, 0.05, 0.5]))
+        X = inp.host_normal_f32((n, d), 1.0, int(rng.integers(1, 10 ** 6)))
+        Gf = inp.host_normal_f32((n, d), 0.3, int(rng.integers(1, 10 ** 6)))
+        G = inp.f32_to_bf16_bits(Gf) if bf16 else Gf
+        Gt = torch.from_numpy(G.view(np.int16) if bf16 else G).to("cuda:0")
+        if pitched:
+            pad = int(rng.choice([0, 1, 4, 13, 64]))          # odd pads leave rows unaligned for 128-bit access
+            px = 3 * d + pad
+            pool = torch.zeros(n * px + 8, dtype=torch.float32, device="cuda:0")
+            Xd = pool.as_strided((n, d), (px, 1), 0)
+            Yd = Xd if in_place else pool.as_strided((n, d), (px, 1), d)
+            Xd.copy_(torch.from_numpy(X))
+            if bf16:
+                Gd = pool.view(torch.int16).as_strided((n, d), (2 * px, 1), 4 * d)
+            else:
+                Gd = pool.as_strided((n, d), (px, 1), 2 * d)
+            Gd.copy_(Gt)
+        else:
+            Xd = torch.from_numpy(X).to("cuda:0")
+            Yd = Xd if in_place else torch.full_like(Xd, float("nan"))
+            Gd = Gt
+        c = torch.full((1,), float("nan"), dtype=torch.float64, device="cuda:0")
+        psgd.mix_step(Xd, Yd, Gd, torch.from_numpy(nbr).to("cuda:0"), torch.from_numpy(w).to("cuda:0"), lr,
+                      cdist_out=c if want_cd else None)
+        torch.cuda.synchronize()
+        got = Yd.cpu().numpy()
+        want = orc.mix_step(X, G, orc.densify(nbr, w), lr)
+        label = (block, case, n, d, nbr.shape[1], bf16, pitched, in_place, want_cd, lr)
+        scale = max(np.abs(want).max(), 1e-30)
+        tol = REL * max(1.0, roundings / 4)
+        assert np.abs(got - want).max() <= tol * scale, label
+        assert np.linalg.norm(got - want) <= tol * max(np.linalg.norm(want), 1e-30), label
+        if want_cd:
+            c_ref = orc.consensus_dist(got)
+            assert abs(c.item() - c_ref) <= REL * c_ref + 1e-300, label
+    assert psgd.device_status() == 0
