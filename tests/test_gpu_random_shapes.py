@@ -86,3 +86,57 @@ def test_random_cases(psgd, block):
             c_ref = orc.consensus_dist(got)
             assert abs(c.item() - c_ref) <= REL * c_ref + 1e-300, label
     assert psgd.device_status() == 0
+
+
+@pytest.mark.parametrize("block", range(6))
+def test_random_cases_global_average_distance_and_producer(psgd, block):
+    """Same sweep for the table-free calls: global averaging, the distance kernels (dense and
+    pitched) and the delayed workload's gradient producer."""
+    rng = np.random.default_rng(5000 + block)
+    for case in range(30):
+        n = int(rng.choice([1, 2, 3, 5, 8, 16, 31, 64, 128, 300, 512]))
+        d = int(rng.choice([1, 2, 4, 7, 64, 257, 1024, 3000, 10_004]))
+        if n * d > 2_000_000:
+            d = max(1, 2_000_000 // n)
+        bf16 = bool(rng.integers(0, 2))
+        in_place = bool(rng.integers(0, 2))
+        pad = int(rng.choice([0, 0, 3, 4, 32]))
+        px = 3 * d + pad
+        lr = float(rng.choice([0.0, 0.1, 1.0]))
+        offset = float(rng.choice([0.0, 100.0]))              # replicas far from the origin
+        X = (inp.host_normal_f32((n, d), 1.0, int(rng.integers(1, 10 ** 6))) + np.float32(offset)).astype(np.float32)
+        Gf = inp.host_normal_f32((n, d), 0.3, int(rng.integers(1, 10 ** 6)))
+        G = inp.f32_to_bf16_bits(Gf) if bf16 else Gf
+        pool = torch.zeros(n * px + 8, dtype=torch.float32, device="cuda:0")
+        Xd = pool.as_strided((n, d), (px, 1), 0)
+        Yd = Xd if in_place else pool.as_strided((n, d), (px, 1), d)
+        Xd.copy_(torch.from_numpy(X))
+        if bf16:
+            Gd = pool.view(torch.int16).as_strided((n, d), (2 * px, 1), 4 * d)
+            Gd.copy_(torch.from_numpy(G.view(np.int16)))
+        else:
+            Gd = pool.as_strided((n, d), (px, 1), 2 * d)
+            Gd.copy_(torch.from_numpy(G))
+        label = (block, case, n, d, bf16, in_place, pad, lr, offset)
+        c = torch.full((2,), float("nan"), dtype=torch.float64, device="cuda:0")
+        psgd.consensus_dist_async(Xd, c[0:1])
+        psgd.mix_full(Xd, Yd, Gd, lr, cdist_out=c[1:2])
+        torch.cuda.synchronize()
+        c0 = orc.consensus_dist(X)
+        assert abs(c[0].item() - c0) <= REL * c0 + 1e-300, label
+        got = Yd.cpu().numpy()
+        want = orc.mix_step(X, G, orc.uniform_matrix(n), lr)
+        scale = max(np.abs(want).max(), 1e-30)
+        assert np.abs(got - want).max() <= REL * scale, label
+        c1 = orc.consensus_dist(got)
+        assert abs(c[1].item() - c1) <= REL * c1 + 1e-300, label
+        # producer: G' = c * Y + noise into a fresh pitched array
+        noise = inp.host_normal_f32((n, d), 0.5, int(rng.integers(1, 10 ** 6)))
+        pool2 = torch.zeros(n * (2 * d + pad) + 8, dtype=torch.float32, device="cuda:0")
+        Nd = pool2.as_strided((n, d), (2 * d + pad, 1), 0)
+        Od = pool2.as_strided((n, d), (2 * d + pad, 1), d)
+        Nd.copy_(torch.from_numpy(noise))
+        psgd.synth_grad(Yd, Nd, Od, 0.25)
+        torch.cuda.synchronize()
+        wantg = orc.synth_grad(got, noise, 0.25)
+        assert np.abs(Od.cpu().numpy() - wantg).max() <= 2.0 ** -23 * max(np.abs(wantg).max(), 1e-30), label
