@@ -111,6 +111,20 @@ def _stream_handle(stream):
     return ctypes.c_void_p(stream.cuda_stream)
 
 
+def _on_current_device(*tensors):
+    """Every pointer handed to the library must be device memory of the CURRENT device: a host
+    pointer or another GPU's would be dereferenced by a kernel."""
+    import torch
+    if not torch.cuda.is_available():
+        raise ValueError("no GPU visible: the library works on device memory only")
+    cur = torch.cuda.current_device()
+    for t in tensors:
+        if t is None:
+            continue
+        if not isinstance(t, torch.Tensor) or not t.is_cuda or t.device.index != cur:
+            raise ValueError("expected tensors on the current GPU (cuda:%d)" % cur)
+
+
 def _rows_cols(t):
     if t.dim() != 2 or not t.is_contiguous():
         raise ValueError("expected a contiguous [n, d] tensor")
@@ -143,6 +157,7 @@ def build_mixing_device(topology, n, seed, nbr, w, step_dev=None, step_offset=0,
     if nbr.dtype != torch.int32 or w.dtype != torch.float32 or nbr.numel() != 3 * n or w.numel() != 3 * n \
             or not nbr.is_contiguous() or not w.is_contiguous():
         raise ValueError("nbr must be int32 [n,3] and w float32 [n,3], contiguous")
+    _on_current_device(nbr, w, step_dev)
     sp = None
     if step_dev is not None:
         if step_dev.dtype not in (torch.int64, torch.uint64) or step_dev.numel() < 1 or step_dev.device != nbr.device:
@@ -172,9 +187,7 @@ def mix_step(X, X_out, G, nbr, w, lr, delay_mode=0, stream=None, cdist_out=None)
             or not nbr.is_contiguous() or not w.is_contiguous():
         raise ValueError("nbr must be int32 [n,deg] and w float32 [n,deg], contiguous")
     deg = nbr.numel() // n
-    for t in (X_out, G, nbr, w):
-        if t.device != X.device:
-            raise ValueError("all tensors must live on one device")
+    _on_current_device(X, X_out, G, nbr, w, cdist_out)
     lib = load()
     if G.dtype == torch.float32:
         bf16 = False
@@ -220,6 +233,7 @@ def mix_full(X, X_out, G, lr, delay_mode=0, stream=None, cdist_out=None):
         bf16 = 1
     else:
         raise ValueError("G must be float32 or bfloat16 bit patterns")
+    _on_current_device(X, X_out, G, cdist_out)
     cd_ptr = None
     if cdist_out is not None:
         if cdist_out.dtype != torch.float64 or cdist_out.numel() < 1 or cdist_out.device != X.device:
@@ -231,7 +245,11 @@ def mix_full(X, X_out, G, lr, delay_mode=0, stream=None, cdist_out=None):
 
 def consensus_dist(X):
     """Synchronous sum_i ||x_i - xbar||^2 of a device tensor [n, d]."""
+    import torch
     n, d = _rows_cols(X)
+    _on_current_device(X)
+    if X.dtype != torch.float32:
+        raise ValueError("X must be float32")
     v = load().psgd_consensus_dist(X.data_ptr(), n, d)
     if math.isnan(v):
         err = last_error()
@@ -244,6 +262,9 @@ def consensus_dist_async(X, out, stream=None):
     """Enqueue the consensus distance of X into out (device float64 tensor, 1 element)."""
     import torch
     n, d, ldx = _rows_cols_pitch(X)
+    _on_current_device(X, out)
+    if X.dtype != torch.float32:
+        raise ValueError("X must be float32")
     if out.dtype != torch.float64 or out.numel() < 1 or out.device != X.device:
         raise ValueError("out must be a float64 device tensor")
     if ldx != d:
@@ -255,8 +276,12 @@ def consensus_dist_async(X, out, stream=None):
 def synth_grad(X_prev, noise, G, c, stream=None):
     """Enqueue G = c * X_prev + noise (fp32, elementwise) for the delay-by-one workload.
     Contiguous tensors of any shape, or [n, d] tensors with pitched rows."""
+    import torch
     if X_prev.shape != noise.shape or X_prev.shape != G.shape:
         raise ValueError("X_prev, noise and G must have one shape")
+    _on_current_device(X_prev, noise, G)
+    if X_prev.dtype != torch.float32 or noise.dtype != torch.float32 or G.dtype != torch.float32:
+        raise ValueError("X_prev, noise and G must be float32")
     if X_prev.is_contiguous() and noise.is_contiguous() and G.is_contiguous():
         _check(load().psgd_synth_grad(X_prev.data_ptr(), noise.data_ptr(), G.data_ptr(), X_prev.numel(),
                                       float(c), _stream_handle(stream)))

@@ -740,3 +740,25 @@ def test_graph_of_table_build_and_step_walks_the_iterations(psgd):
         c_ref = orc.consensus_dist(got)
         assert abs(c.item() - c_ref) <= REL * c_ref
         assert abs(psgd.consensus_dist(X) - c_ref) <= REL * c_ref          # eager work between replays
+
+
+def test_binding_checks_dtypes_and_devices(psgd):
+    n, d = 4, 64
+    X = torch.zeros(n, d, device="cuda:0")
+    nbr, w = psgd.build_mixing(psgd.TOPO_RING, n)
+    nb, wd = dev(nbr), dev(w)
+    with pytest.raises(ValueError):
+        psgd.mix_step(X.cpu(), X.clone(), X.clone(), nb, wd, 0.1)              # host X
+    with pytest.raises(ValueError):
+        psgd.mix_step(X, X.clone(), X.clone(), nb.cpu(), wd, 0.1)              # host table
+    with pytest.raises(ValueError):
+        psgd.mix_step(X, X.clone(), X.double(), nb, wd, 0.1)                   # fp64 gradients
+    with pytest.raises(ValueError):
+        psgd.mix_step(X.half(), X.clone(), X.clone(), nb, wd, 0.1)
+    with pytest.raises(ValueError):
+        psgd.synth_grad(X.bfloat16(), X.bfloat16(), X.bfloat16(), 0.1)          # 2-byte elements
+    with pytest.raises(ValueError):
+        psgd.consensus_dist(X.double())
+    with pytest.raises(ValueError):
+        psgd.mix_step(X, X.clone(), X.clone(), nb, wd, 0.1, cdist_out=torch.zeros(1, device="cuda:0"))   # fp32 distance
+    assert psgd.device_status() == 0

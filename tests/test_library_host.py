@@ -213,3 +213,24 @@ def test_pitched_overlap_verdict_matches_brute_force():
         assert (rc == psgd.EALIAS) == brute, (n, d, P, Pb, a0, b0, rc, brute)
         hits += brute
     assert 50 < hits < 350
+
+
+def test_binding_refuses_host_tensors():
+    """The binding hands raw pointers to kernels, so anything that is not memory of the current
+    GPU must be stopped in Python (here, or on a GPU machine, a host tensor would otherwise fault)."""
+    import torch
+    n, d = 4, 16
+    X = torch.zeros(n, d)
+    nbr, w = psgd.build_mixing(psgd.TOPO_RING, n)
+    with pytest.raises(ValueError):
+        psgd.mix_step(X, X.clone(), X.clone(), torch.from_numpy(nbr), torch.from_numpy(w), 0.1)
+    with pytest.raises(ValueError):
+        psgd.mix_full(X, X.clone(), X.clone(), 0.1)
+    with pytest.raises(ValueError):
+        psgd.consensus_dist(X)
+    with pytest.raises(ValueError):
+        psgd.consensus_dist_async(X, torch.zeros(1, dtype=torch.float64))
+    with pytest.raises(ValueError):
+        psgd.synth_grad(X, X.clone(), X.clone(), 0.1)
+    with pytest.raises(ValueError):
+        psgd.build_mixing_device(psgd.TOPO_RING, n, 0, torch.from_numpy(nbr), torch.from_numpy(w))
