@@ -320,3 +320,40 @@ def test_cfg5_dense_layout_full_size(psgd):
     assert psgd.consensus_dist(X) == wl.d * wl.n * (wl.n ** 2 - 1) / 12
     del X
     torch.cuda.empty_cache()
+
+
+def test_rows_longer_than_2_31_elements(psgd):
+    """Column indices beyond 2^31 (d = 2^31 + 1028, n = 2; the workloads only exercise row offsets
+    beyond 2^32): ring walk, tiled path, global average and the distance, on sampled columns that
+    include both ends of the row."""
+    n, d, lr = 2, 2 ** 31 + 1028, 0.25
+    X = inp.device_normal_f32((n, d), 1.0, 71)
+    Y = torch.empty_like(X)
+    G = inp.device_normal_bf16((n, d), 0.5, 72)
+    cols = inp.sample_columns(d, SAMPLE, seed=73)
+    assert cols.max() == d - 1 and (cols > 2 ** 31).sum() >= 8
+    cols_t = torch.from_numpy(cols).to("cuda:0")
+    Xo, Go = pull(X, cols_t), pull(G, cols_t)
+    c = torch.zeros(3, dtype=torch.float64, device="cuda:0")
+    nbr, w = psgd.build_mixing(psgd.TOPO_RAND_RING, n, 5, 0)              # n = 2: self 1/3, other 2/3
+    psgd.mix_step(X, Y, G, dev(nbr), dev(w), lr, cdist_out=c[0:1])
+    assert_close(pull(Y, cols_t), orc.mix_step(Xo, Go, orc.densify(nbr, w), lr))
+    # closed form for n = 2: the distance is half the squared difference of the two rows
+    want_c = 0.0
+    for lo in range(0, d, 2 ** 28):                      # the subtraction in fp64: an fp32 difference would round
+        diff = Y[0, lo:lo + 2 ** 28].double() - Y[1, lo:lo + 2 ** 28].double()
+        want_c += 0.5 * float((diff * diff).sum().item())
+    del diff
+    torch.cuda.synchronize()
+    assert abs(c[0].item() - want_c) <= 1e-9 * want_c
+    gen = np.array([[0, 1, 1], [1, 0, 0]], dtype=np.int32)                # not a ring by the slot rule: tiled path
+    wg = np.array([[0.5, 0.25, 0.25], [0.5, 0.3, 0.2]], dtype=np.float32)
+    psgd.mix_step(X, Y, G, dev(gen), dev(wg), lr, cdist_out=c[1:2])
+    assert_close(pull(Y, cols_t), orc.mix_step(Xo, Go, orc.densify(gen, wg), lr))
+    psgd.mix_full(X, Y, G, lr, cdist_out=c[2:3])
+    assert_close(pull(Y, cols_t), orc.mix_step(Xo, Go, orc.uniform_matrix(n), lr))
+    torch.cuda.synchronize()
+    chk = psgd.consensus_dist(Y)
+    assert abs(c[2].item() - chk) <= 1e-9 * chk and psgd.device_status() == 0
+    del X, Y, G
+    torch.cuda.empty_cache()
