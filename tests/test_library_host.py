@@ -186,9 +186,9 @@ def test_no_device_is_reported_not_crashed():
     assert rc == psgd.EHIP and psgd.last_error() != ""
 
 
-def test_pitched_overlap_verdict_matches_brute_force():
+def test_pitched_overlap_answer_matches_brute_force():
     """The alias check of the row-pitched entry points against a plain double loop over all row
-    pairs, on random interleavings (fake addresses: the verdict is reached before any device call)."""
+    pairs, on random interleavings (fake addresses: the answer is given before any device call)."""
     lib = psgd.load()
     rng = np.random.default_rng(3)
     T1, T2 = 0x7000000000, 0x7000001000
