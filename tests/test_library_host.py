@@ -234,3 +234,37 @@ def test_binding_refuses_host_tensors():
         psgd.synth_grad(X, X.clone(), X.clone(), 0.1)
     with pytest.raises(ValueError):
         psgd.build_mixing_device(psgd.TOPO_RING, n, 0, torch.from_numpy(nbr), torch.from_numpy(w))
+
+
+def test_host_calls_are_thread_safe_and_errors_are_per_thread():
+    import threading
+    lib = psgd.load()
+    results, errors = {}, {}
+
+    def good(k):
+        for rep in range(50):
+            nbr, w = psgd.build_mixing(psgd.TOPO_RAND_RING, 64, 1000 + k, rep)
+            if not np.array_equal(nbr, orc.neighbour_table(orc.TOPO_RAND_RING, 64, 1000 + k, rep)[0]):
+                results[k] = False
+                return
+        results[k] = True
+
+    def bad(k):
+        nbr = (ctypes.c_int32 * 12)()
+        w = (ctypes.c_float * 12)()
+        for rep in range(200):
+            rc = lib.psgd_build_mixing(0, -k - 1, 0, 0, nbr, w)
+            text = psgd.last_error()
+            if rc != psgd.EINVAL or ("n=%d " % (-k - 1)) not in text:
+                errors[k] = text
+                return
+        errors[k] = None
+
+    ts = [threading.Thread(target=good, args=(k,)) for k in range(4)] + \
+         [threading.Thread(target=bad, args=(k,)) for k in range(4)]
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join()
+    assert all(results[k] for k in range(4))
+    assert all(errors[k] is None for k in range(4)), errors
