@@ -80,8 +80,13 @@ def test_random_cases(psgd, block):
         label = (block, case, n, d, nbr.shape[1], bf16, pitched, in_place, want_cd, lr)
         scale = max(np.abs(want).max(), 1e-30)
         tol = REL * max(1.0, roundings / 4)
-        assert np.abs(got - want).max() <= tol * scale, label
-        assert np.linalg.norm(got - want) <= tol * max(np.linalg.norm(want), 1e-30), label
+        # With a handful of columns the outputs can cancel to far below the inputs (n = 3, d = 1: every row
+        # is the mean of three numbers of size 2 that sum to 0.01).  The arithmetic then sets the floor: one
+        # rounding per slot and one for the gradient term, each on a partial sum bounded by |X|max + lr |G|max.
+        gmax = np.abs(orc.bf16_bits_to_f64(G)).max() if bf16 else np.abs(Gf).max()
+        floor = roundings * 2.0 ** -24 * (np.abs(X).max() + lr * gmax)
+        assert np.abs(got - want).max() <= max(tol * scale, floor), label
+        assert np.linalg.norm(got - want) <= max(tol * np.linalg.norm(want), floor * np.sqrt(n * d)), label
         if want_cd:
             c_ref = orc.consensus_dist(got)
             assert abs(c.item() - c_ref) <= REL * c_ref + 1e-300, label
