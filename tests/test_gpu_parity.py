@@ -762,3 +762,36 @@ def test_binding_checks_dtypes_and_devices(psgd):
     with pytest.raises(ValueError):
         psgd.mix_step(X, X.clone(), X.clone(), nb, wd, 0.1, cdist_out=torch.zeros(1, device="cuda:0"))   # fp32 distance
     assert psgd.device_status() == 0
+
+
+@pytest.mark.parametrize("kind", ["ring", "general3", "deg5", "full"])
+@pytest.mark.parametrize("n,d", [(4, 8_000_004), (4, 6_000_001), (16, 2_000_004), (16, 1_500_001)])
+def test_many_sweeps_per_workgroup(psgd, kind, n, d):
+    """Rows long enough that every persistent workgroup strides over many column groups /
+    tiles (the small shapes finish in one), with a ragged last tile; every element is compared.
+    n = 16 takes the tiled kernel's variant without per-row guards, n = 4 the guarded one."""
+    lr = 0.1
+    rng = np.random.default_rng(d % 1000 + len(kind))
+    X = inp.host_normal_f32((n, d), 1.0, 61)
+    G = inp.f32_to_bf16_bits(inp.host_normal_f32((n, d), 0.5, 62))
+    Xd, Gd = dev(X), bits_dev(G)
+    Yd = torch.full_like(Xd, float("nan"))
+    c = torch.full((1,), float("nan"), dtype=torch.float64, device="cuda:0")
+    if kind == "full":
+        T = orc.uniform_matrix(n)
+        psgd.mix_full(Xd, Yd, Gd, lr, cdist_out=c)
+    else:
+        if kind == "ring":
+            nbr, w = psgd.build_mixing(psgd.TOPO_RAND_RING, n, 3, 4)
+        elif kind == "general3":
+            nbr, w = _general_table(n, rng)
+        else:
+            nbr, w = _perm_sum_table(n, 5, rng)
+        T = orc.densify(nbr, w)
+        psgd.mix_step(Xd, Yd, Gd, dev(nbr), dev(w), lr, cdist_out=c)
+    torch.cuda.synchronize()
+    got = Yd.cpu().numpy()
+    assert_close(got, orc.mix_step(X, G, T, lr), rel=REL * (1.5 if kind == "deg5" else 1.0))
+    c_ref = orc.consensus_dist(got)
+    assert abs(c.item() - c_ref) <= REL * c_ref
+    assert psgd.device_status() == 0
