@@ -27,6 +27,8 @@ namespace psgd {
 namespace {
 
 constexpr int kThreads = 256;        // 4 wavefronts of 64 lanes
+constexpr int kRingThreads = 768;    // workgroup of the step kernel: its wavefronts walk the ring in lockstep, so a row
+                                     // receives one contiguous burst of kRingThreads * 16 bytes at a time
 constexpr int kTileBytes = 32 * 1024;  // LDS budget of the tiled path per workgroup
 constexpr int kUnroll = 8;           // rows whose loads are in flight together per lane
 constexpr int kTileUnroll = 4;     // rows whose loads a lane of the tiled path keeps in flight (8 would cost a
@@ -153,11 +155,12 @@ enum TableKind { kTableBad = 0, kTableRing = 1, kTableGeneral = 2 };
 // bijection, and following it from learner 0 visits all n learners.  The last property is
 // decided by parallel list ranking (pointer doubling) toward learner 0's left neighbour;
 // the resulting distances are the ring positions, used to fill `ring` in walk order.
+template <int T>
 __device__ int stage_table(const int32_t* __restrict__ nbr, const float* __restrict__ w, int n,
                            const Lds& l) {
     const int tid = threadIdx.x;
     int ok = 1;
-    for (int e = tid; e < 3 * n; e += kThreads) {
+    for (int e = tid; e < 3 * n; e += T) {
         const int v = nbr[e];
         l.nbr[e] = v;
         l.w[e] = w[e];
@@ -166,7 +169,7 @@ __device__ int stage_table(const int32_t* __restrict__ nbr, const float* __restr
     if (!__syncthreads_and(ok)) return kTableBad;
 
     int ring = 1;
-    for (int i = tid; i < n; i += kThreads) {
+    for (int i = tid; i < n; i += T) {
         const int left = l.nbr[3 * i + 1], right = l.nbr[3 * i + 2];
         ring &= (l.nbr[3 * i] == i) & (l.nbr[3 * right + 1] == i) & (l.nbr[3 * left + 2] == i);
     }
@@ -177,13 +180,13 @@ __device__ int stage_table(const int32_t* __restrict__ nbr, const float* __restr
     int* nxt_b = dst_a + n;
     int* dst_b = nxt_b + n;
     const int tail = l.nbr[1];  // learner 0's left neighbour ends the list that starts at 0
-    for (int i = tid; i < n; i += kThreads) {
+    for (int i = tid; i < n; i += T) {
         nxt_a[i] = (i == tail) ? i : l.nbr[3 * i + 2];
         dst_a[i] = (i == tail) ? 0 : 1;
     }
     __syncthreads();
     for (int span = 1; span < n; span <<= 1) {
-        for (int i = tid; i < n; i += kThreads) {
+        for (int i = tid; i < n; i += T) {
             const int j = nxt_a[i];
             nxt_b[i] = nxt_a[j];
             dst_b[i] = dst_a[i] + dst_a[j];
@@ -193,9 +196,9 @@ __device__ int stage_table(const int32_t* __restrict__ nbr, const float* __restr
         t = dst_a; dst_a = dst_b; dst_b = t;
     }
     int reached = 1;
-    for (int i = tid; i < n; i += kThreads) reached &= (nxt_a[i] == tail);
+    for (int i = tid; i < n; i += T) reached &= (nxt_a[i] == tail);
     if (!__syncthreads_and(reached)) return kTableGeneral;
-    for (int i = tid; i < n; i += kThreads) {
+    for (int i = tid; i < n; i += T) {
         const int pos = n - 1 - dst_a[i];
         RingEnt e;
         e.row = i;
@@ -221,13 +224,18 @@ __device__ __forceinline__ double wave_sum(double v) {
     return v;
 }
 
-__device__ __forceinline__ double block_sum(double v, double* lds4) {
+// Sum over the workgroup (T threads); the per-wavefront sums are added in a fixed order.
+template <int T = kThreads>
+__device__ __forceinline__ double block_sum(double v, double* lds_waves) {
     v = wave_sum(v);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    if (lane == 0) lds4[wave] = v;
+    if (lane == 0) lds_waves[wave] = v;
     __syncthreads();
     double r = 0.0;
-    if (threadIdx.x == 0) r = (lds4[0] + lds4[1]) + (lds4[2] + lds4[3]);
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int i = 0; i < T / 64; i += 2) r += lds_waves[i] + lds_waves[i + 1];
+    }
     return r;  // valid in thread 0
 }
 
@@ -254,28 +262,40 @@ __device__ __forceinline__ void pivot_of(f32x4 x, double* s) {
     for (int k = 0; k < 4; ++k) s[k] = (double)x[k];
 }
 
-// Running sums of one lane's column group; the first value it is given becomes the pivot.
+// Running sums of one lane's column group; the first value it is given becomes the pivot (kept as
+// the fp32 value it is).  The squares of all the group's columns share one accumulator: only their
+// total is needed, and registers are what limits the size of the step kernel's workgroups.
 template <int VEC>
 struct ColStats {
-    double s[VEC], a[VEC], b[VEC];
+    typename Cols<VEC>::T s;
+    double a[VEC], sq;
     int have;
     __device__ __forceinline__ void reset() {
         have = 0;
+        sq = 0.0;
 #pragma unroll
-        for (int k = 0; k < VEC; ++k) a[k] = b[k] = 0.0;
+        for (int k = 0; k < VEC; ++k) a[k] = 0.0;
     }
     __device__ __forceinline__ void add(typename Cols<VEC>::T x) {
         if (!have) {
-            pivot_of(x, s);
+            s = x;
             have = 1;
         } else {
-            acc_diff<VEC>(a, b, x, s);
+            double xs[VEC], ps[VEC];
+            pivot_of(x, xs);
+            pivot_of(s, ps);
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) {
+                const double df = xs[k] - ps[k];
+                a[k] += df;
+                sq = fma(df, df, sq);
+            }
         }
     }
     __device__ __forceinline__ double result(double inv_n) const {
-        double t = 0.0;
+        double t = sq;
 #pragma unroll
-        for (int k = 0; k < VEC; ++k) t += b[k] - a[k] * a[k] * inv_n;
+        for (int k = 0; k < VEC; ++k) t -= a[k] * a[k] * inv_n;
         return t;
     }
 };
@@ -286,10 +306,16 @@ struct ColStats {
 // in registers for the wrap-around, so every X element is loaded exactly once and, when
 // X_out aliases X, always before the store that replaces it.
 // ---------------------------------------------------------------------------------------
+//
+// The workgroup's wavefronts are kept on the same batch of rows by a barrier per batch: each row
+// then receives one contiguous burst of (workgroup size) * 16 bytes, which the HBM serves a little
+// faster than the same bytes arriving wavefront by wavefront.  Every lane of the workgroup therefore
+// walks the ring the same number of times; a lane without a column group of its own (`act` false,
+// ragged end of the row) shadows a valid group with its loads and stores nothing.
 template <int VEC, typename GT, bool CD>
 __device__ __forceinline__ void ring_walk(const float* xc, float* oc, const GT* __restrict__ gc,
                                           const RingEnt* ring, int n, Pitch ld, float neg_lr,
-                                          ColStats<VEC>& stats) {
+                                          ColStats<VEC>& stats, bool act) {
     typedef typename Cols<VEC>::T V;
     const Cols<VEC> tag{};
     const V first = ld_x(xc + (int64_t)ring_row(ring) * ld.x, tag);
@@ -299,6 +325,7 @@ __device__ __forceinline__ void ring_walk(const float* xc, float* oc, const GT* 
     // Whole batches: positions p .. p+U-1, whose right neighbours p+1 .. p+U are all fresh
     // loads (none of them is position n-1 or the wrap to position 0).
     for (; p + kUnroll <= n - 2; p += kUnroll) {
+        __syncthreads();
         RingEnt e[kUnroll];
         V xs[kUnroll], gs[kUnroll];
 #pragma unroll
@@ -310,7 +337,7 @@ __device__ __forceinline__ void ring_walk(const float* xc, float* oc, const GT* 
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const V out = mix_one<V>(e[u].w0, e[u].w1, e[u].w2, cur, prev, xs[u], gs[u], neg_lr);
-            st_x(oc + (int64_t)e[u].row * ld.o, out);
+            if (act) st_x(oc + (int64_t)e[u].row * ld.o, out);
             if (CD) stats.add(out);
             prev = cur;
             cur = xs[u];
@@ -335,7 +362,7 @@ __device__ __forceinline__ void ring_walk(const float* xc, float* oc, const GT* 
         for (int u = 0; u < kUnroll; ++u) {
             if (p + u < n) {
                 const V out = mix_one<V>(e[u].w0, e[u].w1, e[u].w2, cur, prev, xs[u], gs[u], neg_lr);
-                st_x(oc + (int64_t)e[u].row * ld.o, out);
+                if (act) st_x(oc + (int64_t)e[u].row * ld.o, out);
                 if (CD) stats.add(out);
                 prev = cur;
                 cur = xs[u];
@@ -351,8 +378,8 @@ __device__ __forceinline__ void ring_walk(const float* xc, float* oc, const GT* 
 // ---------------------------------------------------------------------------------------
 // Extra LDS of the tiled path when it also gathers the consensus statistics: one partial
 // column sum per wavefront and column.
-__host__ __device__ inline size_t tile_cd_bytes(int lpr, int vec) {
-    return 8 + (size_t)(kThreads / 64) * lpr * vec * sizeof(double);
+__host__ __device__ inline size_t tile_cd_bytes(int lpr, int vec, int threads = kThreads) {
+    return 8 + (size_t)(threads / 64) * lpr * vec * sizeof(double);
 }
 
 // One output group from the tile: slots in table order, acc = w0 * x0, then one fma per
@@ -379,18 +406,18 @@ __device__ __forceinline__ V mix_slots(const V* tile, const IT* nbr, const float
 // of row 0, which every row group computes for itself (bit-identical: same tile, same table,
 // same gradient bits; the extra read of G's row 0 is served by the cache).  The squares then
 // add up lane by lane and only the plain sums need merging per column, through LDS.
-template <int VEC, typename GT, bool CD, typename IT, bool FULL = false>
+template <int VEC, typename GT, bool CD, typename IT, bool FULL = false, int T = kThreads>
 __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ G, const Lds& l, const IT* nbr_tab,
                             int n, Pitch ld, int64_t ncg, float neg_lr, int lpr, double inv_n, int deg = 3) {
     typedef typename Cols<VEC>::T V;
     const Cols<VEC> tag{};
     constexpr int U = kTileUnroll;
     V* tile = reinterpret_cast<V*>(l.scratch);
-    // [4 wavefronts][lpr][VEC] doubles (CD only), 8-byte aligned behind the tile.  The offset is
+    // [T / 64 wavefronts][lpr][VEC] doubles (CD only), 8-byte aligned behind the tile.  The offset is
     // rounded, not the pointer: a pointer that has been through an integer loses its LDS
     // address space and every access through it becomes a (slow) generic-address instruction.
     double* comb = reinterpret_cast<double*>(l.scratch + (((size_t)n * lpr * sizeof(V) + 7) & ~(size_t)7));
-    const int lane = threadIdx.x % lpr, rg = threadIdx.x / lpr, nrg = kThreads / lpr;
+    const int lane = threadIdx.x % lpr, rg = threadIdx.x / lpr, nrg = T / lpr;
     const int64_t ntiles = (ncg + lpr - 1) / lpr;
     double total = 0.0;
     for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
@@ -473,8 +500,10 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
         if (CD && active && rg == 0) {
 #pragma unroll
             for (int k = 0; k < VEC; ++k) {
-                const double at = (comb[(size_t)lane * VEC + k] + comb[(size_t)(lpr + lane) * VEC + k]) +
-                                  (comb[(size_t)(2 * lpr + lane) * VEC + k] + comb[(size_t)(3 * lpr + lane) * VEC + k]);
+                double at = 0.0;
+#pragma unroll
+                for (int q = 0; q < T / 64; q += 2)
+                    at += comb[(size_t)(q * lpr + lane) * VEC + k] + comb[(size_t)((q + 1) * lpr + lane) * VEC + k];
                 total -= at * at * inv_n;
             }
         }
@@ -483,17 +512,17 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
 }
 
 // CD = also reduce the consensus distance of the outputs into partials[blockIdx.x].
-template <int VEC, typename GT, bool CD>
-__global__ __launch_bounds__(kThreads) void mix_step_kernel(const float* X, float* Xout,
-                                                            const GT* __restrict__ G,
-                                                            const int32_t* __restrict__ nbr,
-                                                            const float* __restrict__ w, int n, int64_t d,
-                                                            Pitch ld, float neg_lr, int lpr,
-                                                            double* __restrict__ partials) {
+// T = workgroup size: kRingThreads on long rows, kThreads (four workgroups per CU) where the row is too
+// short to give every CU a large workgroup's worth of column groups twice over.
+template <int VEC, typename GT, bool CD, int T>
+__global__ __launch_bounds__(T) void mix_step_kernel(const float* X, float* Xout, const GT* __restrict__ G,
+                                                     const int32_t* __restrict__ nbr, const float* __restrict__ w,
+                                                     int n, int64_t d, Pitch ld, float neg_lr, int lpr,
+                                                     double* __restrict__ partials) {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-    __shared__ double lds4[4];
+    __shared__ double lds_waves[T / 64];
     const Lds l = carve(lds_raw, n);
-    const int kind = stage_table(nbr, w, n, l);
+    const int kind = stage_table<T>(nbr, w, n, l);
     if (kind == kTableBad) {
         if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&g_status_word, 1);
         if (CD && threadIdx.x == 0) partials[blockIdx.x] = __builtin_nan("");
@@ -503,19 +532,21 @@ __global__ __launch_bounds__(kThreads) void mix_step_kernel(const float* X, floa
     const double inv_n = 1.0 / (double)n;
     double total = 0.0;
     if (kind == kTableRing) {
-        const int64_t stride = (int64_t)gridDim.x * kThreads;
-        for (int64_t cg = (int64_t)blockIdx.x * kThreads + threadIdx.x; cg < ncg; cg += stride) {
-            const int64_t col = cg * VEC;
+        const int64_t stride = (int64_t)gridDim.x * T;
+        for (int64_t base = (int64_t)blockIdx.x * T; base < ncg; base += stride) {   // uniform per workgroup
+            const int64_t cg = base + threadIdx.x;
+            const bool act = cg < ncg;
+            const int64_t col = (act ? cg : base) * VEC;
             ColStats<VEC> stats;
             if (CD) stats.reset();
-            ring_walk<VEC, GT, CD>(X + col, Xout + col, G + col, l.ring, n, ld, neg_lr, stats);
-            if (CD) total += stats.result(inv_n);
+            ring_walk<VEC, GT, CD>(X + col, Xout + col, G + col, l.ring, n, ld, neg_lr, stats, act);
+            if (CD && act) total += stats.result(inv_n);
         }
     } else {
-        total = tile_path<VEC, GT, CD>(X, Xout, G, l, l.nbr, n, ld, ncg, neg_lr, lpr, inv_n);
+        total = tile_path<VEC, GT, CD, int, false, T>(X, Xout, G, l, l.nbr, n, ld, ncg, neg_lr, lpr, inv_n);
     }
     if (CD) {
-        const double bs = block_sum(total, lds4);
+        const double bs = block_sum<T>(total, lds_waves);
         if (threadIdx.x == 0) partials[blockIdx.x] = bs;
     }
 }
@@ -814,8 +845,8 @@ inline bool overlaps(const void* a, size_t abytes, const void* b, size_t bbytes)
     return a0 < b0 + bbytes && b0 < a0 + abytes;
 }
 
-inline int persistent_grid(const DeviceInfo& di, int64_t work_items, int per_cu) {
-    int64_t need = (work_items + kThreads - 1) / kThreads;
+inline int persistent_grid(const DeviceInfo& di, int64_t work_items, int per_cu, int threads = kThreads) {
+    int64_t need = (work_items + threads - 1) / threads;
     int64_t cap = (int64_t)di.cus * per_cu;
     if (cap > kMaxGrid) cap = kMaxGrid;
     int64_t g = need < cap ? need : cap;
@@ -853,7 +884,7 @@ bool rows_overlap(const void* A, int64_t lda, size_t ra, const void* B, int64_t 
 
 // Workgroups of `fn` (256 threads, `lds_bytes` of dynamic LDS) that fit one compute unit, as the
 // runtime computes it from the kernel's registers and LDS; remembered per (kernel, LDS size).
-int resident_per_cu(const void* fn, size_t lds_bytes) {
+int resident_per_cu(const void* fn, size_t lds_bytes, int threads = kThreads) {
     struct Entry {
         const void* fn;
         size_t lds;
@@ -866,7 +897,7 @@ int resident_per_cu(const void* fn, size_t lds_bytes) {
     for (int i = 0; i < used; ++i)
         if (cache[i].fn == fn && cache[i].lds == lds_bytes) return cache[i].occ;
     int q = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&q, fn, kThreads, lds_bytes) != hipSuccess || q < 1) q = 1;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&q, fn, threads, lds_bytes) != hipSuccess || q < 1) q = 1;
     if (used < 32) cache[used++] = Entry{fn, lds_bytes, q};
     return q;
 }
@@ -884,16 +915,29 @@ bool scalar_overlaps(const double* p, const void* B, int64_t ldb, size_t rb, int
 // Launches one instantiation of the mix kernel on a persistent grid sized to what is
 // actually resident: min(kGridPerCu, occupancy for this LDS size) workgroups per CU.
 // Returns the grid size.
-template <int VEC, typename GT, bool CD>
-int launch_mix(const DeviceInfo& di, size_t lds_bytes, hipStream_t s, const float* X, float* X_out, const GT* G,
-               const int32_t* nbr, const float* w, int n, int64_t d, Pitch ld, float neg_lr, int lpr,
-               double* partials) {
-    const int occ = resident_per_cu(reinterpret_cast<const void*>(mix_step_kernel<VEC, GT, CD>), lds_bytes);
-    const int per_cu = occ < kGridPerCu ? occ : kGridPerCu;
-    const int grid = persistent_grid(di, d / VEC, per_cu);
-    hipLaunchKernelGGL((mix_step_kernel<VEC, GT, CD>), dim3(grid), dim3(kThreads), lds_bytes, s, X, X_out, G, nbr, w, n,
-                       d, ld, neg_lr, lpr, partials);
+template <int VEC, typename GT, bool CD, int T>
+int launch_mix_t(const DeviceInfo& di, size_t lds_bytes, hipStream_t s, const float* X, float* X_out, const GT* G,
+                 const int32_t* nbr, const float* w, int n, int64_t d, Pitch ld, float neg_lr, int lpr,
+                 double* partials) {
+    const int occ = resident_per_cu(reinterpret_cast<const void*>(mix_step_kernel<VEC, GT, CD, T>), lds_bytes, T);
+    const int want = T == kThreads ? kGridPerCu : 1;
+    const int grid = persistent_grid(di, d / VEC, occ < want ? occ : want, T);
+    hipLaunchKernelGGL((mix_step_kernel<VEC, GT, CD, T>), dim3(grid), dim3(T), lds_bytes, s, X, X_out, G, nbr, w, n, d,
+                       ld, neg_lr, lpr, partials);
     return grid;
+}
+
+// Long rows take the large lockstep workgroup.
+inline bool long_rows(const DeviceInfo& di, int64_t column_groups) {
+    return column_groups >= (int64_t)di.cus * kRingThreads * 2;
+}
+
+template <int VEC, typename GT, bool CD>
+int launch_mix(const DeviceInfo& di, bool big, size_t lds_bytes, hipStream_t s, const float* X, float* X_out,
+               const GT* G, const int32_t* nbr, const float* w, int n, int64_t d, Pitch ld, float neg_lr, int lpr,
+               double* partials) {
+    return big ? launch_mix_t<VEC, GT, CD, kRingThreads>(di, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials)
+               : launch_mix_t<VEC, GT, CD, kThreads>(di, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials);
 }
 
 int consensus_enqueue(const float* X, int64_t ldx, int n, int64_t d, double* out_dev, hipStream_t s);
@@ -948,13 +992,15 @@ int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
     // Tile shape of the tiled path: widest power-of-two lane count whose tile (plus the
     // combine arrays of the fused distance) fits the budget and the 64 KB a workgroup may use.
     const size_t lds_limit = deg == 3 ? 64 * 1024 - 64 : kDegLdsLimit;   // wide tables may need more than 64 KB
+    const bool big = deg == 3 && long_rows(*di, d / vec);
+    const int wg_threads = big ? kRingThreads : kThreads;
     const size_t table_bytes = (lds_table_bytes(n, deg) + 15) & ~(size_t)15;
     const size_t tile_budget = (size_t)kTileBytes;
     int lpr = 64;
     size_t scratch_bytes = 0;
     for (;; lpr >>= 1) {
         const size_t tile = (size_t)n * lpr * vec * sizeof(float);
-        scratch_bytes = tile + (want_cd ? tile_cd_bytes(lpr, vec) : 0);
+        scratch_bytes = tile + (want_cd ? tile_cd_bytes(lpr, vec, wg_threads) : 0);
         if ((tile <= tile_budget && table_bytes + scratch_bytes <= lds_limit) || lpr == 1) break;
     }
     if (scratch_bytes < (size_t)n * 4 * sizeof(int)) scratch_bytes = (size_t)n * 4 * sizeof(int);
@@ -993,13 +1039,13 @@ int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
             hipLaunchKernelGGL((mix_deg_kernel<1, GT, false>), g, b, lds_bytes, s, X, X_out, G, nbr, w, deg, n, d, ld,
                                neg_lr, lpr, partials);
     } else if (vec4 && want_cd)
-        grid = launch_mix<4, GT, true>(*di, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials);
+        grid = launch_mix<4, GT, true>(*di, big, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials);
     else if (vec4)
-        grid = launch_mix<4, GT, false>(*di, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials);
+        grid = launch_mix<4, GT, false>(*di, big, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials);
     else if (want_cd)
-        grid = launch_mix<1, GT, true>(*di, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials);
+        grid = launch_mix<1, GT, true>(*di, big, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials);
     else
-        grid = launch_mix<1, GT, false>(*di, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials);
+        grid = launch_mix<1, GT, false>(*di, big, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, name);
     if (want_cd) {
