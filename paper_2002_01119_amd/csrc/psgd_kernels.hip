@@ -604,19 +604,23 @@ __device__ __forceinline__ f32x4 mean_of(const double* s, double inv_n, Cols<4>)
     return (f32x4){(float)(s[0] * inv_n), (float)(s[1] * inv_n), (float)(s[2] * inv_n), (float)(s[3] * inv_n)};
 }
 
-template <int VEC, typename GT, bool CD>
-__global__ __launch_bounds__(kThreads) void mix_full_kernel(const float* X, float* Xout, const GT* __restrict__ G,
-                                                            int n, int64_t d, Pitch ld, float neg_lr,
-                                                            double* __restrict__ partials) {
+// T = workgroup size, chosen as for the ring step: on long rows a large workgroup whose wavefronts
+// sweep the rows in lockstep (a barrier per batch), so each row sees one long contiguous burst.
+template <int VEC, typename GT, bool CD, int T>
+__global__ __launch_bounds__(T) void mix_full_kernel(const float* X, float* Xout, const GT* __restrict__ G, int n,
+                                                     int64_t d, Pitch ld, float neg_lr,
+                                                     double* __restrict__ partials) {
     typedef typename Cols<VEC>::T V;
     const Cols<VEC> tag{};
-    __shared__ double lds4[4];
+    __shared__ double lds_waves[T / 64];
     const int64_t ncg = d / VEC;
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    const int64_t stride = (int64_t)gridDim.x * T;
     const double inv_n = 1.0 / (double)n;
     double total = 0.0;
-    for (int64_t cg = (int64_t)blockIdx.x * kThreads + threadIdx.x; cg < ncg; cg += stride) {
-        const int64_t col = cg * VEC;
+    for (int64_t base = (int64_t)blockIdx.x * T; base < ncg; base += stride) {   // uniform per workgroup
+        const int64_t cg = base + threadIdx.x;
+        const bool act = cg < ncg;           // a lane past the end shadows the workgroup's first group and stores nothing
+        const int64_t col = (act ? cg : base) * VEC;
         const float* xc = X + col;
         const GT* gc = G + col;
         float* oc = Xout + col;
@@ -625,6 +629,7 @@ __global__ __launch_bounds__(kThreads) void mix_full_kernel(const float* X, floa
         for (int k = 0; k < VEC; ++k) sum[k] = 0.0;
         int r = 0;
         for (; r + kUnroll <= n; r += kUnroll) {
+            __syncthreads();
             V xs[kUnroll];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) xs[u] = ld_x(xc + (int64_t)(r + u) * ld.x, tag);
@@ -637,25 +642,26 @@ __global__ __launch_bounds__(kThreads) void mix_full_kernel(const float* X, floa
         if (CD) stats.reset();
         r = 0;
         for (; r + kUnroll <= n; r += kUnroll) {
+            __syncthreads();
             V gs[kUnroll];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) gs[u] = ld_g(gc + (int64_t)(r + u) * ld.g, tag);
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
                 const V out = vfma(neg_lr, gs[u], mean);
-                st_x(oc + (int64_t)(r + u) * ld.o, out);
+                if (act) st_x(oc + (int64_t)(r + u) * ld.o, out);
                 if (CD) stats.add(out);
             }
         }
         for (; r < n; ++r) {
             const V out = vfma(neg_lr, ld_g(gc + (int64_t)r * ld.g, tag), mean);
-            st_x(oc + (int64_t)r * ld.o, out);
+            if (act) st_x(oc + (int64_t)r * ld.o, out);
             if (CD) stats.add(out);
         }
-        if (CD) total += stats.result(inv_n);
+        if (CD && act) total += stats.result(inv_n);
     }
     if (CD) {
-        const double bs = block_sum(total, lds4);
+        const double bs = block_sum<T>(total, lds_waves);
         if (threadIdx.x == 0) partials[blockIdx.x] = bs;
     }
 }
@@ -927,9 +933,10 @@ int launch_mix_t(const DeviceInfo& di, size_t lds_bytes, hipStream_t s, const fl
     return grid;
 }
 
-// Long rows take the large lockstep workgroup.
-inline bool long_rows(const DeviceInfo& di, int64_t column_groups) {
-    return column_groups >= (int64_t)di.cus * kRingThreads * 2;
+// Long rows take the large lockstep workgroup: at least `sweeps` column groups per lane of one such
+// workgroup per CU (measured: the ring step gains from 2 sweeps on, the global average from about 16).
+inline bool long_rows(const DeviceInfo& di, int64_t column_groups, int sweeps = 2) {
+    return column_groups >= (int64_t)di.cus * kRingThreads * sweeps;
 }
 
 template <int VEC, typename GT, bool CD>
@@ -1096,19 +1103,31 @@ int mix_full_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
     if (int rc = device_info(&di, want_cd)) return rc;
     const bool vec4 = (d % 4 == 0) && (ldx % 4 == 0) && (ldo % 4 == 0) && (ldg % 4 == 0) && aligned_to(X, 16) &&
                       aligned_to(X_out, 16) && aligned_to(G, 4 * sizeof(GT));
-    const int grid = persistent_grid(*di, vec4 ? d / 4 : d, kGridPerCu);
-    const dim3 g(grid), b(kThreads);
+    const bool big = long_rows(*di, vec4 ? d / 4 : d, 16);
+    const int grid = big ? persistent_grid(*di, vec4 ? d / 4 : d, 1, kRingThreads)
+                         : persistent_grid(*di, vec4 ? d / 4 : d, kGridPerCu);
+    const dim3 g(grid), b(big ? kRingThreads : kThreads);
     const Pitch ld{ldx, ldo, ldg};
     const float neg_lr = -lr;
     double* partials = want_cd ? di->scratch : nullptr;
+#define PSGD_LAUNCH_FULL(VEC, CD)                                                                                          \
+    do {                                                                                                                   \
+        if (big)                                                                                                           \
+            hipLaunchKernelGGL((mix_full_kernel<VEC, GT, CD, kRingThreads>), g, b, 0, s, X, X_out, G, n, d, ld, neg_lr,     \
+                               partials);                                                                                  \
+        else                                                                                                               \
+            hipLaunchKernelGGL((mix_full_kernel<VEC, GT, CD, kThreads>), g, b, 0, s, X, X_out, G, n, d, ld, neg_lr,         \
+                               partials);                                                                                  \
+    } while (0)
     if (vec4 && want_cd)
-        hipLaunchKernelGGL((mix_full_kernel<4, GT, true>), g, b, 0, s, X, X_out, G, n, d, ld, neg_lr, partials);
+        PSGD_LAUNCH_FULL(4, true);
     else if (vec4)
-        hipLaunchKernelGGL((mix_full_kernel<4, GT, false>), g, b, 0, s, X, X_out, G, n, d, ld, neg_lr, partials);
+        PSGD_LAUNCH_FULL(4, false);
     else if (want_cd)
-        hipLaunchKernelGGL((mix_full_kernel<1, GT, true>), g, b, 0, s, X, X_out, G, n, d, ld, neg_lr, partials);
+        PSGD_LAUNCH_FULL(1, true);
     else
-        hipLaunchKernelGGL((mix_full_kernel<1, GT, false>), g, b, 0, s, X, X_out, G, n, d, ld, neg_lr, partials);
+        PSGD_LAUNCH_FULL(1, false);
+#undef PSGD_LAUNCH_FULL
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, name);
     if (want_cd) {
