@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0
 # chip (factor 2.000), WRITE_SIZE reads them all (factor 1.000).  Workloads not yet measured
 # report null.
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg5_n64_d100M_bf16g_randring", "ring"): (18_750_600 * 2.000 + 25_000_000 * 1.000) * 1024,
+    ("cfg5_n64_d100M_bf16g_randring", "ring"): (18_750_609 * 2.000 + 25_000_166 * 1.000) * 1024,
     ("cfg5_n64_d100M_bf16g_randring", "degree5"): (18_751_856 * 2.000 + 25_000_067 * 1.000) * 1024,
     ("cfg5_n64_d100M_bf16g_randring", "degree9"): (18_750_863 * 2.000 + 25_000_033 * 1.000) * 1024,
     ("cfg5_n64_d100M_bf16g_randring", "full"): (18_750_535 * 2.000 + 25_000_558 * 1.000) * 1024,
