@@ -795,3 +795,27 @@ def test_many_sweeps_per_workgroup(psgd, kind, n, d):
     c_ref = orc.consensus_dist(got)
     assert abs(c.item() - c_ref) <= REL * c_ref
     assert psgd.device_status() == 0
+
+
+@pytest.mark.parametrize("gkind", ["f32", "bf16"])
+def test_global_average_large_workgroups_every_element(psgd, gkind):
+    """Rows long enough for the global-average kernel's large lockstep workgroups (they start at
+    16 column groups per lane), ragged end included; every element and the distance compared."""
+    n, d, lr = 4, 16_000_004, 0.2
+    X = inp.host_normal_f32((n, d), 1.0, 81)
+    G = inp.host_normal_f32((n, d), 0.5, 82)
+    if gkind == "bf16":
+        G = inp.f32_to_bf16_bits(G)
+    Xd = dev(X)
+    Gd = bits_dev(G) if gkind == "bf16" else dev(G)
+    c = torch.full((1,), float("nan"), dtype=torch.float64, device="cuda:0")
+    Yd = torch.full_like(Xd, float("nan"))
+    psgd.mix_full(Xd, Yd, Gd, lr, cdist_out=c)
+    torch.cuda.synchronize()
+    got = Yd.cpu().numpy()
+    assert_close(got, orc.mix_step(X, G, orc.uniform_matrix(n), lr))
+    c_ref = orc.consensus_dist(got)
+    assert abs(c.item() - c_ref) <= REL * c_ref
+    psgd.mix_full(Xd, Xd, Gd, lr)                     # in place, no distance
+    torch.cuda.synchronize()
+    assert torch.equal(Xd, Yd)
