@@ -166,8 +166,8 @@ int psgd_mix_step_cd_bf16g(const float* X, float* X_out, const uint16_t* G_bf16,
  * path needs d and all three pitches to be multiples of 4.
  *
  * Why pitches: (1) a column shard of a wider array is such a view; (2) placement.  On
- * MI355X this step was measured at 63-66 % of the HBM peak when each array is one dense
- * block of a few tens of GB, and at 74-76 % when the rows of every array are pitched a few
+ * MI355X this step was measured at 65-72 % of the HBM peak when each array is one dense
+ * block of a few tens of GB, and at 76-78 % when the rows of every array are pitched a few
  * GB apart (other arrays' rows in between) so that the rows in flight cover most of the
  * device's address range.
  */

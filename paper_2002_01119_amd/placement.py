@@ -4,7 +4,7 @@ On MI355X the sustained rate of a kernel that writes a multi-gigabyte buffer dep
 that buffer lies: ranges of the same size, carved from one allocation, fall into a faster
 (about 6 TB/s of stores) and a slower (about 5 TB/s) class, reproducibly for a given range and
 independently of the order in which it is swept.  The mixing step follows the class of its
-output buffer (74-77 % against 63-65 % of the 8 TB/s peak).  Nothing in the public
+output buffer (76-78 % against 65-72 % of the 8 TB/s peak).  Nothing in the public
 documentation predicts the class from an address, so it is measured: allocate one pool, time
 the step itself, in place, on candidate windows of the pool, and put the buffers that are
 written every iteration (X and X_out) on the fastest non-overlapping windows.  Buffers that
