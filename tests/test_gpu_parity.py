@@ -819,3 +819,23 @@ def test_global_average_large_workgroups_every_element(psgd, gkind):
     psgd.mix_full(Xd, Xd, Gd, lr)                     # in place, no distance
     torch.cuda.synchronize()
     assert torch.equal(Xd, Yd)
+
+
+def test_status_flag_is_sticky_until_cleared_and_long_rows_refuse_bad_tables(psgd):
+    n, d = 4, 2_000_000                      # long rows: the large-workgroup variant of the step kernel
+    nbr, w = psgd.build_mixing(psgd.TOPO_RING, n)
+    bad = nbr.copy()
+    bad[1, 2] = -1
+    X = torch.ones(n, d, device="cuda:0")
+    Y = torch.full_like(X, float("nan"))
+    c = torch.zeros(1, dtype=torch.float64, device="cuda:0")
+    psgd.mix_step(X, Y, X.clone(), dev(bad), dev(w), 0.1, cdist_out=c)
+    torch.cuda.synchronize()
+    assert torch.isnan(Y).all() and np.isnan(c.item())
+    assert psgd.device_status(clear=False) == 1
+    assert psgd.device_status(clear=False) == 1          # still raised
+    psgd.mix_step(X, Y, X.clone(), dev(nbr), dev(w), 0.1, cdist_out=c)      # a good step does not lower it
+    torch.cuda.synchronize()
+    assert not torch.isnan(Y).any() and c.item() == 0.0
+    assert psgd.device_status(clear=True) == 1
+    assert psgd.device_status() == 0
