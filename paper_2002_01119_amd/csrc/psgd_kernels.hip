@@ -957,7 +957,7 @@ int launch_mix_t(const DeviceInfo& di, size_t lds_bytes, hipStream_t s, const fl
 }
 
 // Long rows take the large lockstep workgroup: at least `sweeps` column groups per lane of one such
-// workgroup per CU (measured: the ring step gains from 2 sweeps on, the global average from about 16).
+// workgroup per CU.
 inline bool long_rows(const DeviceInfo& di, int64_t column_groups, int sweeps = 2) {
     return column_groups >= (int64_t)di.cus * kRingThreads * sweeps;
 }
@@ -1126,7 +1126,7 @@ int mix_full_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
     if (int rc = device_info(&di, want_cd)) return rc;
     const bool vec4 = (d % 4 == 0) && (ldx % 4 == 0) && (ldo % 4 == 0) && (ldg % 4 == 0) && aligned_to(X, 16) &&
                       aligned_to(X_out, 16) && aligned_to(G, 4 * sizeof(GT));
-    const bool big = long_rows(*di, vec4 ? d / 4 : d, 16);
+    const bool big = long_rows(*di, vec4 ? d / 4 : d, 2);
     const int grid = big ? persistent_grid(*di, vec4 ? d / 4 : d, 1, kRingThreads)
                          : persistent_grid(*di, vec4 ? d / 4 : d, kGridPerCu);
     const dim3 g(grid), b(big ? kRingThreads : kThreads);
