@@ -524,16 +524,23 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
 constexpr int kChunkAlign = 16;
 struct Sweeps {
     int64_t count, chunk;
-    __device__ __forceinline__ Sweeps(int64_t ncg, int threads) {
-        const int64_t per = (int64_t)gridDim.x * threads;
-        count = (ncg + per - 1) / per;
-        const int64_t parts = count * gridDim.x;
-        chunk = (ncg + parts - 1) / parts;
-        chunk = (chunk + kChunkAlign - 1) / kChunkAlign * kChunkAlign;   // keep every workgroup's range aligned
-    }
     // first column group of this workgroup in sweep sw
     __device__ __forceinline__ int64_t base(int64_t sw) const { return (sw * gridDim.x + blockIdx.x) * chunk; }
 };
+// Computed by the launcher (the device would pay two 64-bit divisions per lane for it).
+inline Sweeps make_sweeps(int64_t ncg, int grid, int threads) {
+    Sweeps s;
+    const int64_t per = (int64_t)grid * threads;
+    s.count = (ncg + per - 1) / per;
+    if (s.count < 4) {   // a launch of one to three sweeps is bound by latency: full chunks, fewer of them
+        s.chunk = threads;
+        return s;
+    }
+    const int64_t parts = s.count * grid;
+    s.chunk = (ncg + parts - 1) / parts;
+    s.chunk = (s.chunk + kChunkAlign - 1) / kChunkAlign * kChunkAlign;   // keep every workgroup's range aligned
+    return s;
+}
 
 // T = workgroup size: kRingThreads on long rows, kThreads (four workgroups per CU) where the row is too
 // short to give every CU a large workgroup's worth of column groups twice over.
@@ -541,7 +548,7 @@ template <int VEC, typename GT, bool CD, int T>
 __global__ __launch_bounds__(T) void mix_step_kernel(const float* X, float* Xout, const GT* __restrict__ G,
                                                      const int32_t* __restrict__ nbr, const float* __restrict__ w,
                                                      int n, int64_t d, Pitch ld, float neg_lr, int lpr,
-                                                     double* __restrict__ partials) {
+                                                     Sweeps sweeps, double* __restrict__ partials) {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     __shared__ double lds_waves[T / 64];
     const Lds l = carve(lds_raw, n);
@@ -555,10 +562,11 @@ __global__ __launch_bounds__(T) void mix_step_kernel(const float* X, float* Xout
     const double inv_n = 1.0 / (double)n;
     double total = 0.0;
     if (kind == kTableRing) {
-        const Sweeps sweeps(ncg, T);
-        for (int64_t sw = 0; sw < sweeps.count; ++sw) {          // the same count for every workgroup
-            const int64_t cg = sweeps.base(sw) + threadIdx.x;
-            const bool act = threadIdx.x < sweeps.chunk && cg < ncg;
+        for (int64_t sw = 0; sw < sweeps.count; ++sw) {
+            const int64_t base = sweeps.base(sw), cg = base + threadIdx.x;
+            if (base >= ncg) break;                              // nothing left for this workgroup (uniform)
+            const int64_t end = base + sweeps.chunk < ncg ? base + sweeps.chunk : ncg;   // uniform
+            const bool act = cg < end;
             const int64_t col = (act ? cg : 0) * VEC;            // idle lanes shadow column group 0
             ColStats<VEC> stats;
             if (CD) stats.reset();
@@ -631,7 +639,7 @@ __device__ __forceinline__ f32x4 mean_of(const double* s, double inv_n, Cols<4>)
 // sweep the rows in lockstep (a barrier per batch), so each row sees one long contiguous burst.
 template <int VEC, typename GT, bool CD, int T>
 __global__ __launch_bounds__(T) void mix_full_kernel(const float* X, float* Xout, const GT* __restrict__ G, int n,
-                                                     int64_t d, Pitch ld, float neg_lr,
+                                                     int64_t d, Pitch ld, float neg_lr, Sweeps sweeps,
                                                      double* __restrict__ partials) {
     typedef typename Cols<VEC>::T V;
     const Cols<VEC> tag{};
@@ -639,10 +647,11 @@ __global__ __launch_bounds__(T) void mix_full_kernel(const float* X, float* Xout
     const int64_t ncg = d / VEC;
     const double inv_n = 1.0 / (double)n;
     double total = 0.0;
-    const Sweeps sweeps(ncg, T);
-    for (int64_t sw = 0; sw < sweeps.count; ++sw) {              // the same count for every workgroup
-        const int64_t cg = sweeps.base(sw) + threadIdx.x;
-        const bool act = threadIdx.x < sweeps.chunk && cg < ncg;   // an idle lane shadows column group 0 and stores nothing
+    for (int64_t sw = 0; sw < sweeps.count; ++sw) {
+        const int64_t base = sweeps.base(sw), cg = base + threadIdx.x;
+        if (base >= ncg) break;                                  // nothing left for this workgroup (uniform)
+        const int64_t end = base + sweeps.chunk < ncg ? base + sweeps.chunk : ncg;   // uniform
+        const bool act = cg < end;                               // an idle lane shadows column group 0 and stores nothing
         const int64_t col = (act ? cg : 0) * VEC;
         const float* xc = X + col;
         const GT* gc = G + col;
@@ -952,7 +961,7 @@ int launch_mix_t(const DeviceInfo& di, size_t lds_bytes, hipStream_t s, const fl
     const int want = T == kThreads ? kGridPerCu : 1;
     const int grid = persistent_grid(di, d / VEC, occ < want ? occ : want, T);
     hipLaunchKernelGGL((mix_step_kernel<VEC, GT, CD, T>), dim3(grid), dim3(T), lds_bytes, s, X, X_out, G, nbr, w, n, d,
-                       ld, neg_lr, lpr, partials);
+                       ld, neg_lr, lpr, make_sweeps(d / VEC, grid, T), partials);
     return grid;
 }
 
@@ -1137,10 +1146,10 @@ int mix_full_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
     do {                                                                                                                   \
         if (big)                                                                                                           \
             hipLaunchKernelGGL((mix_full_kernel<VEC, GT, CD, kRingThreads>), g, b, 0, s, X, X_out, G, n, d, ld, neg_lr,     \
-                               partials);                                                                                  \
+                               make_sweeps(d / VEC, grid, kRingThreads), partials);                                        \
         else                                                                                                               \
             hipLaunchKernelGGL((mix_full_kernel<VEC, GT, CD, kThreads>), g, b, 0, s, X, X_out, G, n, d, ld, neg_lr,         \
-                               partials);                                                                                  \
+                               make_sweeps(d / VEC, grid, kThreads), partials);                                            \
     } while (0)
     if (vec4 && want_cd)
         PSGD_LAUNCH_FULL(4, true);

@@ -17,11 +17,26 @@ import torch
 from . import psgd
 
 
-def pitched_layout(n, d, specs, span_bytes, device):
+def settled_pool(nbytes, device):
+    """A uint8 pool of `nbytes`, allocated twice: the first allocation is touched and handed back
+    to the driver, the second is the one returned.  A process that follows a memory-hungry one
+    (a test suite, say) is given whatever pages that one left, and the step then runs about 2 %
+    slower (75.9 instead of 77.9 % of the HBM peak, reproducibly); once the whole pool has been
+    freed in one piece the driver hands out a better-ordered range."""
+    pool = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    pool.zero_()
+    torch.cuda.synchronize(device)
+    del pool
+    torch.cuda.empty_cache()
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def pitched_layout(n, d, specs, span_bytes, device, settle=True):
     """Interleave the rows of several [n, d] arrays in ONE pool so that every array spans
     `span_bytes` of device memory: slot i (at i * pitch) holds row i of each array back to
     back.  `specs` is a list of (name, torch dtype).  Returns (dict name -> [n, d] strided view,
-    pool tensor, pitch in bytes).  Row starts are 4 KB aligned."""
+    pool tensor, pitch in bytes).  Row starts are 4 KB aligned.  With `settle` the pool comes
+    from settled_pool()."""
     def up(v, a):
         return (v + a - 1) // a * a
     offs, cur = {}, 0
@@ -30,7 +45,7 @@ def pitched_layout(n, d, specs, span_bytes, device):
         cur += up(d * torch.empty((), dtype=dt).element_size(), 4096)
     pitch = max(cur, (span_bytes // max(n, 1)) // 4096 * 4096)
     pool_bytes = (n - 1) * pitch + cur
-    pool = torch.empty(pool_bytes, dtype=torch.uint8, device=device)
+    pool = settled_pool(pool_bytes, device) if settle else torch.empty(pool_bytes, dtype=torch.uint8, device=device)
     views = {}
     for name, dt in specs:
         es = torch.empty((), dtype=dt).element_size()
@@ -90,7 +105,7 @@ def place_replica_buffers(n, d, count, G, nbr, w, reserve_bytes, max_pool_bytes=
     pool_bytes = pool_bytes // 4096 * 4096
     if pool_bytes < count * nbytes:
         raise torch.OutOfMemoryError("pool of %d bytes cannot hold %d buffers" % (pool_bytes, count))
-    pool = torch.empty(pool_bytes, dtype=torch.uint8, device=G.device)
+    pool = settled_pool(pool_bytes, G.device)
     pool.zero_()
     timings = probe_windows(pool, n, d, G, nbr, w, step)
     chosen = choose_windows(timings, nbytes, count)

@@ -102,7 +102,7 @@ def run_workload(psgd, wl, topo, steps=None, layout="dense"):
         if wl.delay:
             specs += [("Xprev", torch.float32), ("noise", torch.float32)]
         total_mem = torch.cuda.mem_get_info()[1]
-        views, pool, pitch = plc.pitched_layout(n, d, specs, int(0.65 * total_mem), "cuda:0")
+        views, pool, pitch = plc.pitched_layout(n, d, specs, int(0.65 * total_mem), "cuda:0", settle=False)
         assert views["X"].stride(0) * 4 == pitch and pitch > d * 4
         X, Y, Gbuf = views["X"], views["Y"], views["G"]
         X.copy_(inp.device_normal_f32((n, d), wl.sigma_x, wl.seed_x))
