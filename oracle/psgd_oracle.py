@@ -23,6 +23,10 @@ Pins (tests/test_oracle_pins.py, all CPU):
                          equal to the fixed ring's, E[T^T T] entries (Eq. 10) and the
                          expected Frobenius contraction (Eq. 11) by enumeration of all L!
                          permutations
+  densify                asymmetric tables typed out entry by entry (one-slot cyclic shift, a
+                         two-slot 3/4-1/4 table, repeated slots), gather-add scalar loops on
+                         random asymmetric tables; planted transposed / overwriting / slot-dropping
+                         mutants are caught
   mix_step               element-by-element triple loop, asymmetric shift matrix,
                          n = 1 reduces to Eq. 1, T_u gives the column mean, mean recurrence
   consensus_dist         closed forms (equal rows -> 0; X[i,j] = i -> d n (n^2-1)/12),

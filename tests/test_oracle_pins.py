@@ -589,6 +589,103 @@ def test_planted_mistakes_are_caught():
         assert _pins_for_mix(m) > 0, name
 
 
+# ------------------------------------------------------------------ slot table -> dense matrix
+def _pins_for_densify(densify):
+    """Orientation pins for the table form of T (Sec. 2, Eq. 2: W T, so column i of T holds the weights
+    of the models that feed learner i, and row i of the table lists exactly that column).  Every table
+    here is asymmetric and typed out, so a transposed assignment cannot pass.  Returns the violations."""
+    bad = 0
+    # one slot, learner i takes the model of learner i - 1: the cyclic shift T[m, m+1] = 1
+    n = 5
+    nbr = np.array([[(i - 1) % n] for i in range(n)], dtype=np.int32)
+    w = np.ones((n, 1), dtype=np.float32)
+    shift = np.array([
+        [0, 1, 0, 0, 0],
+        [0, 0, 1, 0, 0],
+        [0, 0, 0, 1, 0],
+        [0, 0, 0, 0, 1],
+        [1, 0, 0, 0, 0],
+    ], dtype=np.float64)
+    T = densify(nbr, w)
+    bad += not np.array_equal(T, shift)
+    X = np.arange(n * 3, dtype=np.float32).reshape(n, 3)
+    out = orc.mix_step(X, np.zeros_like(X), T, 0.0)
+    bad += not all(np.array_equal(out[l], X[(l - 1) % n]) for l in range(n))
+    # two slots, weights 3/4 and 1/4 (exact in fp32), doubly stochastic but not symmetric:
+    # learner 0 <- 3/4 x_0 + 1/4 x_2, learner 1 <- 3/4 x_1 + 1/4 x_0, learner 2 <- 3/4 x_2 + 1/4 x_1
+    nbr2 = np.array([[0, 2], [1, 0], [2, 1]], dtype=np.int32)
+    w2 = np.array([[0.75, 0.25]] * 3, dtype=np.float32)
+    want2 = np.array([
+        [0.75, 0.25, 0.00],     # row m = what learner m's model contributes to learners 0, 1, 2
+        [0.00, 0.75, 0.25],
+        [0.25, 0.00, 0.75],
+    ])
+    T2 = densify(nbr2, w2)
+    bad += not np.array_equal(T2, want2)
+    X2 = np.array([[1.0, 10.0], [2.0, 20.0], [4.0, 40.0]], dtype=np.float32)
+    out2 = orc.mix_step(X2, np.zeros_like(X2), T2, 0.0)
+    bad += not np.array_equal(out2, np.array([[1.75, 17.5], [1.75, 17.5], [3.5, 35.0]]))
+    # a row whose slots repeat a learner adds the shares (the n = 2 ring: self 1/3, other 2/3)
+    T3 = densify(np.array([[0, 1, 1], [1, 0, 0]], dtype=np.int32), np.full((2, 3), 0.25, dtype=np.float32))
+    bad += not np.array_equal(T3, np.array([[0.25, 0.5], [0.5, 0.25]]))
+    # unequal weights inside one row stay with their slot: learner 0 <- 1/2 x_1 + 1/2 x_2 only
+    nbr4 = np.array([[1, 2], [0, 1], [2, 0]], dtype=np.int32)
+    w4 = np.array([[0.5, 0.5], [0.5, 0.5], [0.5, 0.5]], dtype=np.float32)
+    want4 = np.array([
+        [0.0, 0.5, 0.5],
+        [0.5, 0.5, 0.0],
+        [0.5, 0.0, 0.5],
+    ])
+    bad += not np.array_equal(densify(nbr4, w4), want4)
+    return bad
+
+
+def test_densify_orientation_on_asymmetric_tables():
+    assert _pins_for_densify(orc.densify) == 0
+
+
+def test_densify_agrees_with_table_gather_on_random_asymmetric_tables():
+    """Row i of the table is what learner i receives: the gather-add sum_s w[i,s] x[nbr[i,s]] written as
+    scalar loops must equal the dense product with densify's matrix, for tables built from random
+    permutations (slot s of every row comes from one permutation, so T is doubly stochastic, asymmetric)."""
+    rng = np.random.default_rng(21)
+    for n, deg in [(4, 2), (7, 3), (9, 5)]:
+        nbr = np.stack([rng.permutation(n) for _ in range(deg)], axis=1).astype(np.int32)
+        c = rng.random(deg)
+        w = np.tile((c / c.sum()).astype(np.float32), (n, 1))
+        T = orc.densify(nbr, w)
+        assert not np.allclose(T, T.T)
+        assert np.allclose(T.sum(0), T.sum(1)) and np.allclose(T.sum(0), float(w[0].astype(np.float64).sum()))
+        X = rng.standard_normal((n, 4)).astype(np.float32)
+        want = np.zeros((n, 4))
+        for i in range(n):
+            for s in range(deg):
+                for j in range(4):
+                    want[i, j] += float(w[i, s]) * float(X[nbr[i, s], j])
+        assert np.allclose(orc.mix_step(X, np.zeros_like(X), T, 0.0), want, rtol=0, atol=1e-15)
+
+
+def test_densify_planted_mistakes_are_caught():
+    def transposed(nbr, w):
+        return orc.densify(nbr, w).T
+
+    def duplicates_overwrite(nbr, w):
+        nbr, w = np.asarray(nbr), np.asarray(w)
+        T = np.zeros((nbr.shape[0],) * 2)
+        for i in range(nbr.shape[0]):
+            for s in range(nbr.shape[1]):
+                T[int(nbr[i, s]), i] = float(w[i, s])
+        return T
+
+    def last_slot_dropped(nbr, w):
+        nbr, w = np.asarray(nbr), np.asarray(w)
+        return orc.densify(nbr[:, :max(nbr.shape[1] - 1, 1)], w[:, :max(nbr.shape[1] - 1, 1)])
+
+    for name, m in {"transposed": transposed, "duplicates_overwrite": duplicates_overwrite,
+                    "last_slot_dropped": last_slot_dropped}.items():
+        assert _pins_for_densify(m) > 0, name
+
+
 def test_golden_tables_still_match_oracle(golden_dir):
     """The frozen tables were written by the oracle; a drift in its generator shows here."""
     with open(os.path.join(golden_dir, "mixing_tables.txt")) as f:
