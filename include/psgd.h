@@ -142,8 +142,12 @@ int psgd_mix_step_bf16g(const float* X, float* X_out, const uint16_t* G_bf16,
  * The per-column sums are taken against the column's first output in fp64 and the
  * per-workgroup partials are combined in a fixed order (bit-reproducible; it agrees with
  * psgd_consensus_dist of X_out to rounding, about 1e-13 relative, not bit for bit).
- * Uses the same per-device scratch as psgd_consensus_dist_async, so the same rule holds:
- * calls that may overlap in time on one device must be serialised by the caller.
+ * Uses the same per-device buffer of partial sums as psgd_consensus_dist_async (allocated by
+ * the first such call on a device, which therefore must not happen while `stream` is being
+ * captured into a graph: PSGD_EHIP).  Calls on different streams of one device share it; the
+ * library orders them on the device (the later call's stream waits for the earlier call's last
+ * kernel), so they serialise instead of racing.  Work captured into graphs is exempt: graph
+ * launches that use the buffer must be ordered by the caller.
  * All other arguments, modes and errors are those of psgd_mix_step; d = 0 writes 0.
  */
 int psgd_mix_step_cd(const float* X, float* X_out, const float* G,
@@ -181,7 +185,7 @@ int psgd_mix_step_ex(const float* X, int64_t ldx, float* X_out, int64_t ldo,
  * with `deg` slots per row: X_out[i,:] = sum_{s<deg} w[i*deg+s] * X[nbr[i*deg+s],:] - lr*G[i,:]
  * (nbr, w: device, [n * deg]).  Covers what the 3-slot ring tables cannot: more neighbours per
  * learner, lazy walks, or the product of several mixing rounds collapsed into one matrix (the
- * remedy of the prior work the paper cites in Sec. 6).  1 <= deg <= PSGD_MAX_DEG and
+ * remedy of the prior work the paper cites in Sec. 7).  1 <= deg <= PSGD_MAX_DEG and
  * n * deg <= PSGD_MAX_TABLE.  Per element: acc = w0 * x0; acc = fma(w_s, x_s, acc) for
  * s = 1..deg-1 in table order; out = fma(-lr, g, acc).  deg = 3 is psgd_mix_step_ex (ring
  * tables then take the register walk); other degrees always stage an [n x columns] tile in
@@ -222,9 +226,9 @@ double psgd_consensus_dist(const float* X, int n, int64_t d);
 
 /*
  * psgd_consensus_dist_async - the same value written to out_dev (device, double[1],
- * 8-byte aligned) by work enqueued on `stream`.  Uses a per-device scratch buffer that the
- * library allocates on first use: calls that may run concurrently on one device (two
- * streams) race on it and must be serialised by the caller.
+ * 8-byte aligned) by work enqueued on `stream`.  Uses the per-device buffer of partial sums
+ * described at psgd_mix_step_cd (allocated on first use, not under stream capture; calls from
+ * different streams are serialised on the device).
  */
 int psgd_consensus_dist_async(const float* X, int n, int64_t d, double* out_dev, void* stream);
 

@@ -2,12 +2,62 @@
 #ifndef PSGD_INTERNAL_H
 #define PSGD_INTERNAL_H
 
+#include <cstdint>
+
 namespace psgd {
 
 // Records a printf-style message for psgd_last_error() on this thread and returns `code`.
 int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 void clear_error();
 
+// Launch arithmetic of the persistent grids: plain host functions, kept apart from the kernels so that a CPU
+// build can check them (every column group covered once, grids within the partials buffer).
+namespace plan {
+
+constexpr int kMaxGrid = 4096;    // upper bound on persistent workgroups = slots of the partials buffer
+constexpr int kChunkAlign = 16;   // column groups (256 bytes): ranges that start at an odd 16 bytes cost 7 %
+
+// Workgroups of `threads` lanes for `work_items` lane-sized items: one per item batch, at most `per_cu`
+// per compute unit, never more than kMaxGrid.
+inline int persistent_grid(int cus, int64_t work_items, int per_cu, int threads) {
+    const int64_t need = (work_items + threads - 1) / threads;
+    int64_t cap = (int64_t)cus * per_cu;
+    if (cap > kMaxGrid) cap = kMaxGrid;
+    const int64_t g = need < cap ? need : cap;
+    return (int)(g < 1 ? 1 : g);
+}
+
+// Grid of the degree-K kernel: one workgroup per tile up to what is resident, within the same bound.
+inline int deg_grid(int64_t ntiles, int cus, int per_cu) {
+    int64_t cap = (int64_t)cus * per_cu;
+    if (cap > kMaxGrid) cap = kMaxGrid;
+    const int64_t g = ntiles < cap ? ntiles : cap;
+    return (int)(g < 1 ? 1 : g);
+}
+
+// Even split of `ncg` column groups over a persistent grid: every workgroup makes `count` sweeps and takes
+// `chunk` <= threads consecutive groups in each; workgroup b's range in sweep sw starts at
+// (sw * grid + b) * chunk.  With a fixed chunk of `threads` the last, partly filled sweep costs as much as a
+// full one (11 instead of 10.2 on rows of 2 M groups with 256 workgroups of 768 lanes); the kernels are bound
+// by bytes, so a sweep is as much faster as it is smaller.  The chunk stays a multiple of kChunkAlign.
+struct SweepPlan {
+    int64_t count, chunk;
+};
+inline SweepPlan sweep_plan(int64_t ncg, int grid, int threads) {
+    SweepPlan s;
+    const int64_t per = (int64_t)grid * threads;
+    s.count = (ncg + per - 1) / per;
+    if (s.count < 4) {   // a launch of one to three sweeps is bound by latency: full chunks, fewer of them
+        s.chunk = threads;
+        return s;
+    }
+    const int64_t parts = s.count * grid;
+    s.chunk = (ncg + parts - 1) / parts;
+    s.chunk = (s.chunk + kChunkAlign - 1) / kChunkAlign * kChunkAlign;
+    return s;
+}
+
+}  // namespace plan
 }  // namespace psgd
 
 #endif

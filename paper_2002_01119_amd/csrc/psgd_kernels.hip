@@ -36,7 +36,7 @@ constexpr int kTileBytes = 32 * 1024;  // LDS budget of the tiled path per workg
 constexpr int kUnroll = 8;           // rows whose loads are in flight together per lane
 constexpr int kTileUnroll = 4;     // rows whose loads a lane of the tiled path keeps in flight (8 would cost a
                                    // resident workgroup per CU in registers, which this path needs more)
-constexpr int kMaxGrid = 4096;       // upper bound on persistent workgroups (scratch sizing)
+using plan::kMaxGrid;                // upper bound on persistent workgroups (partials buffer sizing)
 constexpr int kGridPerCu = 4;        // persistent workgroups per compute unit (16 waves per CU)
 constexpr size_t kDegLdsLimit = 96 * 1024;  // LDS a workgroup of the degree-K kernel may ask for (160 KB per CU)
 
@@ -515,13 +515,8 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
 }
 
 // CD = also reduce the consensus distance of the outputs into partials[blockIdx.x].
-// Even split of the column groups over the persistent grid: every workgroup makes the same number
-// of sweeps and takes `chunk` <= T consecutive groups in each, so no sweep is left to a fraction of
-// the workgroups (with a fixed chunk of T the last, partly filled sweep costs as much as a full one:
-// 11 instead of 10.2 on workload 4's rows).  Lanes beyond the chunk idle; the kernel is bound by
-// bytes, so a sweep is as much faster as it is smaller.
-// The chunk is a multiple of 16 column groups (256 bytes): ranges that start at an odd 16 bytes cost 7 %.
-constexpr int kChunkAlign = 16;
+// The column groups are split evenly over the persistent grid (plan::sweep_plan): every workgroup makes the
+// same number of sweeps, lanes beyond the chunk idle.
 struct Sweeps {
     int64_t count, chunk;
     // first column group of this workgroup in sweep sw
@@ -529,17 +524,8 @@ struct Sweeps {
 };
 // Computed by the launcher (the device would pay two 64-bit divisions per lane for it).
 inline Sweeps make_sweeps(int64_t ncg, int grid, int threads) {
-    Sweeps s;
-    const int64_t per = (int64_t)grid * threads;
-    s.count = (ncg + per - 1) / per;
-    if (s.count < 4) {   // a launch of one to three sweeps is bound by latency: full chunks, fewer of them
-        s.chunk = threads;
-        return s;
-    }
-    const int64_t parts = s.count * grid;
-    s.chunk = (ncg + parts - 1) / parts;
-    s.chunk = (s.chunk + kChunkAlign - 1) / kChunkAlign * kChunkAlign;   // keep every workgroup's range aligned
-    return s;
+    const plan::SweepPlan p = plan::sweep_plan(ncg, grid, threads);
+    return Sweeps{p.count, p.chunk};
 }
 
 // T = workgroup size: kRingThreads on long rows, kThreads (four workgroups per CU) where the row is too
@@ -844,7 +830,10 @@ __global__ __launch_bounds__(kThreads) void build_mixing_kernel(int randomize, i
 // ---------------------------------------------------------------------------------------
 struct DeviceInfo {
     int cus = 0;
-    double* scratch = nullptr;  // kMaxGrid partials + 1 result slot
+    double* partials = nullptr;        // hipMalloc'ed on first use: kMaxGrid partials + 1 result slot
+    hipEvent_t partials_idle = nullptr;  // recorded behind the last kernel that read `partials`
+    hipStream_t partials_stream = nullptr;  // the stream that event was recorded on
+    bool partials_used = false;
 };
 constexpr int kMaxDevices = 64;
 DeviceInfo g_dev[kMaxDevices];
@@ -855,7 +844,7 @@ int hip_fail(hipError_t e, const char* what) {
 }
 
 // Looks up (and caches) the current device's compute-unit count.
-int device_info(DeviceInfo** out, bool want_scratch) {
+int device_info(DeviceInfo** out) {
     int dev = -1;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
@@ -868,11 +857,58 @@ int device_info(DeviceInfo** out, bool want_scratch) {
         if (e != hipSuccess) return hip_fail(e, "hipDeviceGetAttribute");
         di.cus = cus > 0 ? cus : 1;
     }
-    if (want_scratch && !di.scratch) {
-        e = hipMalloc(reinterpret_cast<void**>(&di.scratch), sizeof(double) * (kMaxGrid + 1));
-        if (e != hipSuccess) return hip_fail(e, "hipMalloc(scratch)");
-    }
     *out = &di;
+    return PSGD_OK;
+}
+
+bool stream_is_capturing(hipStream_t s) {
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &st) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return st != hipStreamCaptureStatusNone;
+}
+
+// The per-device partials buffer of the fused-distance and consensus calls, handed to work that is about
+// to be enqueued on `s`.  It is allocated on the first call on a device; allocation is not allowed while a
+// stream is being captured, so a first call made under capture is refused with an explanation instead of
+// invalidating the capture.  All calls on a device share the buffer: when the previous user enqueued on
+// another stream, `s` is made to wait (on the device, not on the host) for that user's last kernel, so two
+// streams that both gather a distance are serialised instead of racing.  Streams under capture are left
+// alone: the order of graph launches is the caller's.
+int acquire_partials(DeviceInfo* di, hipStream_t s, double** out) {
+    std::lock_guard<std::mutex> lock(g_dev_mutex);
+    const bool capturing = stream_is_capturing(s);
+    if (!di->partials) {
+        if (capturing)
+            return fail(PSGD_EHIP, "the per-device partials buffer is allocated on first use, which stream capture "
+                                   "forbids: make one fused-distance or consensus call on this device before capturing");
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(&di->partials), sizeof(double) * (kMaxGrid + 1));
+        if (e != hipSuccess) return hip_fail(e, "hipMalloc(partials)");
+        e = hipEventCreateWithFlags(&di->partials_idle, hipEventDisableTiming);
+        if (e != hipSuccess) {
+            (void)hipFree(di->partials);
+            di->partials = nullptr;
+            return hip_fail(e, "hipEventCreateWithFlags");
+        }
+    }
+    if (!capturing && di->partials_used && di->partials_stream != s) {
+        const hipError_t e = hipStreamWaitEvent(s, di->partials_idle, 0);
+        if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent(partials)");
+    }
+    *out = di->partials;
+    return PSGD_OK;
+}
+
+// Called after the last kernel that reads the partials has been enqueued on `s`.
+int release_partials(DeviceInfo* di, hipStream_t s) {
+    std::lock_guard<std::mutex> lock(g_dev_mutex);
+    if (stream_is_capturing(s)) return PSGD_OK;
+    const hipError_t e = hipEventRecord(di->partials_idle, s);
+    if (e != hipSuccess) return hip_fail(e, "hipEventRecord(partials)");
+    di->partials_stream = s;
+    di->partials_used = true;
     return PSGD_OK;
 }
 
@@ -884,12 +920,10 @@ inline bool overlaps(const void* a, size_t abytes, const void* b, size_t bbytes)
 }
 
 inline int persistent_grid(const DeviceInfo& di, int64_t work_items, int per_cu, int threads = kThreads) {
-    int64_t need = (work_items + threads - 1) / threads;
-    int64_t cap = (int64_t)di.cus * per_cu;
-    if (cap > kMaxGrid) cap = kMaxGrid;
-    int64_t g = need < cap ? need : cap;
-    return (int)(g < 1 ? 1 : g);
+    return plan::persistent_grid(di.cus, work_items, per_cu, threads);
 }
+
+using plan::deg_grid;
 
 // True if any row of A ([n] rows of ra bytes, lda bytes apart) shares a byte with any row of B.
 bool rows_overlap(const void* A, int64_t lda, size_t ra, const void* B, int64_t ldb, size_t rb, int n) {
@@ -952,14 +986,16 @@ bool scalar_overlaps(const double* p, const void* B, int64_t ldb, size_t rb, int
 
 // Launches one instantiation of the mix kernel on a persistent grid sized to what is
 // actually resident: min(kGridPerCu, occupancy for this LDS size) workgroups per CU.
-// Returns the grid size.
+// Returns the grid size, or minus the grid size (and launches nothing) when the fused distance would
+// need more than `slots` partials.
 template <int VEC, typename GT, bool CD, int T>
 int launch_mix_t(const DeviceInfo& di, size_t lds_bytes, hipStream_t s, const float* X, float* X_out, const GT* G,
                  const int32_t* nbr, const float* w, int n, int64_t d, Pitch ld, float neg_lr, int lpr,
-                 double* partials) {
+                 double* partials, int slots) {
     const int occ = resident_per_cu(reinterpret_cast<const void*>(mix_step_kernel<VEC, GT, CD, T>), lds_bytes, T);
     const int want = T == kThreads ? kGridPerCu : 1;
     const int grid = persistent_grid(di, d / VEC, occ < want ? occ : want, T);
+    if (CD && grid > slots) return -grid;   // one partial per workgroup must fit the caller's buffer: nothing is launched
     hipLaunchKernelGGL((mix_step_kernel<VEC, GT, CD, T>), dim3(grid), dim3(T), lds_bytes, s, X, X_out, G, nbr, w, n, d,
                        ld, neg_lr, lpr, make_sweeps(d / VEC, grid, T), partials);
     return grid;
@@ -974,12 +1010,11 @@ inline bool long_rows(const DeviceInfo& di, int64_t column_groups, int sweeps = 
 template <int VEC, typename GT, bool CD>
 int launch_mix(const DeviceInfo& di, bool big, size_t lds_bytes, hipStream_t s, const float* X, float* X_out,
                const GT* G, const int32_t* nbr, const float* w, int n, int64_t d, Pitch ld, float neg_lr, int lpr,
-               double* partials) {
-    return big ? launch_mix_t<VEC, GT, CD, kRingThreads>(di, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials)
-               : launch_mix_t<VEC, GT, CD, kThreads>(di, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials);
+               double* partials, int slots) {
+    return big ? launch_mix_t<VEC, GT, CD, kRingThreads>(di, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials, slots)
+               : launch_mix_t<VEC, GT, CD, kThreads>(di, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials, slots);
 }
 
-int consensus_enqueue(const float* X, int64_t ldx, int n, int64_t d, double* out_dev, hipStream_t s);
 
 // Pitches are in elements of the array they belong to.
 template <typename GT>
@@ -1016,14 +1051,18 @@ int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
         return fail(PSGD_EALIAS, "%s: the distance output overlaps a data buffer", name);
     hipStream_t s = static_cast<hipStream_t>(stream);
     DeviceInfo* di = nullptr;
+    if (d == 0 && !want_cd) return PSGD_OK;
+    if (int rc = device_info(&di)) return rc;
+    double* partials = nullptr;
+    const int slots = kMaxGrid;
+    if (want_cd)
+        if (int rc = acquire_partials(di, s, &partials)) return rc;
     if (d == 0) {
-        if (!want_cd) return PSGD_OK;
-        if (int rc = device_info(&di, true)) return rc;
-        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, di->scratch, 0, cd_out);
+        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, partials, 0, cd_out);
         const hipError_t e0 = hipGetLastError();
-        return e0 == hipSuccess ? PSGD_OK : hip_fail(e0, "consensus_final_kernel");
+        if (e0 != hipSuccess) return hip_fail(e0, "consensus_final_kernel");
+        return release_partials(di, s);
     }
-    if (int rc = device_info(&di, want_cd)) return rc;
     // 128-bit path needs every row start 16-byte aligned (8-byte for bf16 gradients).
     const bool vec4 = (d % 4 == 0) && (ldx % 4 == 0) && (ldo % 4 == 0) && (ldg % 4 == 0) && aligned_to(X, 16) &&
                       aligned_to(X_out, 16) && aligned_to(G, 4 * sizeof(GT));
@@ -1049,7 +1088,6 @@ int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
 
     const float neg_lr = -lr;
     const Pitch ld{ldx, ldo, ldg};
-    double* partials = want_cd ? di->scratch : nullptr;
     int grid = 0;
     if (deg != 3) {
         const int64_t ntiles = (d / vec + lpr - 1) / lpr;
@@ -1062,8 +1100,7 @@ int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
         }
         int per_cu = resident_per_cu(fn, lds_bytes);
         if (per_cu > 2 * kGridPerCu) per_cu = 2 * kGridPerCu;
-        const int64_t cap = (int64_t)di->cus * per_cu;
-        grid = (int)(ntiles < cap ? ntiles : cap);
+        grid = deg_grid(ntiles, di->cus, per_cu);
         const dim3 g(grid), b(kThreads);
         if (vec4 && want_cd)
             hipLaunchKernelGGL((mix_deg_kernel<4, GT, true>), g, b, lds_bytes, s, X, X_out, G, nbr, w, deg, n, d, ld,
@@ -1078,19 +1115,21 @@ int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
             hipLaunchKernelGGL((mix_deg_kernel<1, GT, false>), g, b, lds_bytes, s, X, X_out, G, nbr, w, deg, n, d, ld,
                                neg_lr, lpr, partials);
     } else if (vec4 && want_cd)
-        grid = launch_mix<4, GT, true>(*di, big, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials);
+        grid = launch_mix<4, GT, true>(*di, big, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials, slots);
     else if (vec4)
-        grid = launch_mix<4, GT, false>(*di, big, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials);
+        grid = launch_mix<4, GT, false>(*di, big, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials, slots);
     else if (want_cd)
-        grid = launch_mix<1, GT, true>(*di, big, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials);
+        grid = launch_mix<1, GT, true>(*di, big, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials, slots);
     else
-        grid = launch_mix<1, GT, false>(*di, big, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials);
+        grid = launch_mix<1, GT, false>(*di, big, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials, slots);
+    if (grid < 0) return fail(PSGD_EINVAL, "%s: the launch needs %d partial sums", name, -grid);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, name);
     if (want_cd) {
         hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, partials, grid, cd_out);
         e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e, "consensus_final_kernel");
+        return release_partials(di, s);
     }
     return PSGD_OK;
 }
@@ -1125,14 +1164,17 @@ int mix_full_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
         return fail(PSGD_EALIAS, "%s: the distance output overlaps a data buffer", name);
     hipStream_t s = static_cast<hipStream_t>(stream);
     DeviceInfo* di = nullptr;
+    if (d == 0 && !want_cd) return PSGD_OK;
+    if (int rc = device_info(&di)) return rc;
+    double* partials = nullptr;
+    if (want_cd)
+        if (int rc = acquire_partials(di, s, &partials)) return rc;
     if (d == 0) {
-        if (!want_cd) return PSGD_OK;
-        if (int rc = device_info(&di, true)) return rc;
-        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, di->scratch, 0, cd_out);
+        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, partials, 0, cd_out);
         const hipError_t e0 = hipGetLastError();
-        return e0 == hipSuccess ? PSGD_OK : hip_fail(e0, "consensus_final_kernel");
+        if (e0 != hipSuccess) return hip_fail(e0, "consensus_final_kernel");
+        return release_partials(di, s);
     }
-    if (int rc = device_info(&di, want_cd)) return rc;
     const bool vec4 = (d % 4 == 0) && (ldx % 4 == 0) && (ldo % 4 == 0) && (ldg % 4 == 0) && aligned_to(X, 16) &&
                       aligned_to(X_out, 16) && aligned_to(G, 4 * sizeof(GT));
     const bool big = long_rows(*di, vec4 ? d / 4 : d, 2);
@@ -1141,7 +1183,6 @@ int mix_full_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
     const dim3 g(grid), b(big ? kRingThreads : kThreads);
     const Pitch ld{ldx, ldo, ldg};
     const float neg_lr = -lr;
-    double* partials = want_cd ? di->scratch : nullptr;
 #define PSGD_LAUNCH_FULL(VEC, CD)                                                                                          \
     do {                                                                                                                   \
         if (big)                                                                                                           \
@@ -1166,26 +1207,35 @@ int mix_full_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
         hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, partials, grid, cd_out);
         e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e, "consensus_final_kernel");
+        return release_partials(di, s);
     }
     return PSGD_OK;
 }
 
-int consensus_enqueue(const float* X, int64_t ldx, int n, int64_t d, double* out_dev, hipStream_t s) {
+int consensus_enqueue(const float* X, int64_t ldx, int n, int64_t d, double* out_dev, hipStream_t s,
+                      double** result_slot) {
     DeviceInfo* di = nullptr;
-    if (int rc = device_info(&di, true)) return rc;
+    if (int rc = device_info(&di)) return rc;
+    double* partials = nullptr;
+    if (int rc = acquire_partials(di, s, &partials)) return rc;
+    if (result_slot) *result_slot = partials + kMaxGrid;
     const bool vec4 = (d % 4 == 0) && (ldx % 4 == 0) && aligned_to(X, 16);
-    const int grid = persistent_grid(*di, vec4 ? d / 4 : d, 8);  // light kernel: 32 waves per CU
-    if (vec4)
-        hipLaunchKernelGGL(consensus_partial_kernel<4>, dim3(grid), dim3(kThreads), 0, s, X, n, d, ldx, di->scratch);
-    else
-        hipLaunchKernelGGL(consensus_partial_kernel<1>, dim3(grid), dim3(kThreads), 0, s, X, n, d, ldx, di->scratch);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return hip_fail(e, "consensus_partial_kernel");
-    hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, di->scratch, grid,
-                       out_dev ? out_dev : di->scratch + kMaxGrid);
-    e = hipGetLastError();
+    int grid = 0;
+    if (d > 0) {
+        grid = persistent_grid(*di, vec4 ? d / 4 : d, 8);  // light kernel: 32 waves per CU
+        if (vec4)
+            hipLaunchKernelGGL(consensus_partial_kernel<4>, dim3(grid), dim3(kThreads), 0, s, X, n, d, ldx, partials);
+        else
+            hipLaunchKernelGGL(consensus_partial_kernel<1>, dim3(grid), dim3(kThreads), 0, s, X, n, d, ldx, partials);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e, "consensus_partial_kernel");
+    }
+    // d = 0: nothing to reduce, the final kernel over zero partials writes 0
+    hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, partials, grid,
+                       out_dev ? out_dev : partials + kMaxGrid);
+    const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "consensus_final_kernel");
-    return PSGD_OK;
+    return release_partials(di, s);
 }
 
 int consensus_check(const char* name, const float* X, int64_t ldx, int n, int64_t d) {
@@ -1204,17 +1254,7 @@ int consensus_async_impl(const char* name, const float* X, int64_t ldx, int n, i
     if (!out_dev) return fail(PSGD_EINVAL, "%s: null output pointer", name);
     if (!aligned_to(out_dev, 8)) return fail(PSGD_EALIGN, "%s: out_dev not 8-byte aligned", name);
     if (int rc = consensus_check(name, X, ldx, n, d)) return rc;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    if (d == 0) {
-        // nothing to reduce: the final kernel over zero partials writes 0
-        DeviceInfo* di = nullptr;
-        if (int rc = device_info(&di, true)) return rc;
-        hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, di->scratch, 0, out_dev);
-        const hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return hip_fail(e, "consensus_final_kernel");
-        return PSGD_OK;
-    }
-    return consensus_enqueue(X, n == 1 ? d : ldx, n, d, out_dev, s);
+    return consensus_enqueue(X, n == 1 ? d : ldx, n, d, out_dev, static_cast<hipStream_t>(stream), nullptr);
 }
 
 }  // namespace
@@ -1320,11 +1360,10 @@ double psgd_consensus_dist(const float* X, int n, int64_t d) {
     if (d == 0 || n == 1) return 0.0;
     hipError_t e = hipDeviceSynchronize();
     if (e != hipSuccess) { hip_fail(e, "hipDeviceSynchronize"); return NAN; }
-    if (consensus_enqueue(X, d, n, d, nullptr, nullptr) != PSGD_OK) return NAN;
-    DeviceInfo* di = nullptr;
-    if (device_info(&di, true) != PSGD_OK) return NAN;
+    double* slot = nullptr;
+    if (consensus_enqueue(X, d, n, d, nullptr, nullptr, &slot) != PSGD_OK) return NAN;
     double host = NAN;
-    e = hipMemcpy(&host, di->scratch + kMaxGrid, sizeof(double), hipMemcpyDeviceToHost);
+    e = hipMemcpy(&host, slot, sizeof(double), hipMemcpyDeviceToHost);
     if (e != hipSuccess) { hip_fail(e, "hipMemcpy(result)"); return NAN; }
     return host;
 }
@@ -1349,7 +1388,7 @@ int psgd_synth_grad(const float* X_prev, const float* noise, float* G, int64_t c
         return fail(PSGD_EALIAS, "psgd_synth_grad: G overlaps an input");
     if (count == 0) return PSGD_OK;
     DeviceInfo* di = nullptr;
-    if (int rc = device_info(&di, false)) return rc;
+    if (int rc = device_info(&di)) return rc;
     const int vec4 = aligned_to(X_prev, 16) && aligned_to(noise, 16) && aligned_to(G, 16);
     const int grid = persistent_grid(*di, vec4 ? (count + 3) / 4 : count, 16);
     hipLaunchKernelGGL(synth_grad_kernel, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream), X_prev,
@@ -1376,7 +1415,7 @@ int psgd_synth_grad_ex(const float* X_prev, int64_t ldx, const float* noise, int
         return fail(PSGD_EALIAS, "psgd_synth_grad_ex: G overlaps an input");
     if (d == 0) return PSGD_OK;
     DeviceInfo* di = nullptr;
-    if (int rc = device_info(&di, false)) return rc;
+    if (int rc = device_info(&di)) return rc;
     const bool vec4 = d % 4 == 0 && ldx % 4 == 0 && ldn % 4 == 0 && ldg % 4 == 0 && aligned_to(X_prev, 16) &&
                       aligned_to(noise, 16) && aligned_to(G, 16);
     const int grid = persistent_grid(*di, vec4 ? d / 4 : d, 8);

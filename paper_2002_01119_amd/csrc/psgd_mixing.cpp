@@ -5,7 +5,6 @@
 
 #include <cstdarg>
 #include <cstdio>
-#include <vector>
 
 namespace psgd {
 
@@ -37,8 +36,7 @@ struct SplitMix64 {
 
 // sigma[p] = learner at ring position p for iteration `step` (Sec. 4: every learner derives
 // the same ring from the shared seed, so this must depend on (n, seed, step) only).
-void draw_ring(int n, uint64_t seed, uint64_t step, std::vector<int32_t>& sigma) {
-    sigma.resize(n);
+void draw_ring(int n, uint64_t seed, uint64_t step, int32_t* sigma) {
     for (int p = 0; p < n; ++p) sigma[p] = p;
     SplitMix64 rng{seed ^ ((step + 1ull) * 0x9E3779B97F4A7C15ull)};
     for (int i = n - 1; i >= 1; --i) {
@@ -66,11 +64,10 @@ int psgd_build_mixing(int topology, int n, uint64_t seed, uint64_t step, int32_t
     if (topology != PSGD_TOPO_RING && topology != PSGD_TOPO_RAND_RING)
         return fail(PSGD_EINVAL, "psgd_build_mixing: unknown topology %d", topology);
 
-    std::vector<int32_t> sigma;
+    int32_t sigma[PSGD_MAX_N];   // on the stack: nothing here can throw across the C boundary
     if (topology == PSGD_TOPO_RAND_RING) {
         draw_ring(n, seed, step, sigma);
     } else {
-        sigma.resize(n);
         for (int p = 0; p < n; ++p) sigma[p] = p;
     }
     // Walk the ring once: the learner at position p has the learners at p-1 and p+1 as its
@@ -93,6 +90,6 @@ int psgd_build_mixing(int topology, int n, uint64_t seed, uint64_t step, int32_t
 
 const char* psgd_last_error(void) { return psgd::g_err; }
 
-int psgd_version(void) { return 1; }
+int psgd_version(void) { return 2; }
 
 }  // extern "C"

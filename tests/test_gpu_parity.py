@@ -839,3 +839,40 @@ def test_status_flag_is_sticky_until_cleared_and_long_rows_refuse_bad_tables(psg
     assert not torch.isnan(Y).any() and c.item() == 0.0
     assert psgd.device_status(clear=True) == 1
     assert psgd.device_status() == 0
+
+
+def test_two_streams_gathering_distances_are_serialised(psgd):
+    """All fused-distance and consensus calls on a device share one buffer of partial sums.  Calls enqueued
+    back to back on two streams would race on it; the library makes the later stream wait for the earlier
+    call's last kernel, so each distance must be the one of its own output, every time."""
+    n, lr = 16, 0.1
+    shapes = [(n, 1_600_004), (n, 70_001)]            # a long launch on one stream, a short one on the other
+    data = []
+    for i, (nn, d) in enumerate(shapes):
+        X = inp.host_normal_f32((nn, d), 1.0 + i, 300 + i)
+        G = inp.host_normal_f32((nn, d), 0.1, 310 + i)
+        nbr, w = orc.neighbour_table(orc.TOPO_RAND_RING, nn, 5, i)
+        data.append((dev(X), dev(G), dev(nbr), dev(w), X, G, nbr, w))
+    outs = [torch.empty_like(t[0]) for t in data]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    rounds = 6
+    cd = torch.full((rounds, 2), float("nan"), dtype=torch.float64, device="cuda:0")
+    cs = torch.full((rounds, 2), float("nan"), dtype=torch.float64, device="cuda:0")
+    torch.cuda.synchronize()
+    for r in range(rounds):
+        for i in (0, 1):
+            Xd, Gd, nd, wd = data[i][:4]
+            psgd.mix_step(Xd, outs[i], Gd, nd, wd, lr, stream=streams[i], cdist_out=cd[r, i:i + 1])
+        for i in (1, 0):
+            psgd.consensus_dist_async(outs[i], cs[r, i:i + 1], stream=streams[i])
+    torch.cuda.synchronize()
+    got, sep = cd.cpu().numpy(), cs.cpu().numpy()
+    for i in (0, 1):
+        X, G, nbr, w = data[i][4:]
+        want = orc.mix_step(X, G, orc.densify(nbr, w), lr)
+        assert_close(outs[i].cpu().numpy(), want)
+        c_want = orc.consensus_dist(outs[i].cpu().numpy())
+        for r in range(rounds):
+            assert abs(got[r, i] - c_want) <= REL * c_want, (r, i, got[r, i], c_want)
+            assert abs(sep[r, i] - c_want) <= REL * c_want, (r, i, sep[r, i], c_want)
+    assert psgd.device_status() == 0

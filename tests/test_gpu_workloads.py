@@ -309,6 +309,57 @@ def test_cfg5_bf16_gradients_full_size(psgd):
     torch.cuda.empty_cache()
 
 
+def test_cfg5_full_size_every_element_one_step(psgd):
+    """One step of workload 5 at full size, in the benchmark's launch (pitched rows, fused distance, large
+    lockstep workgroups, even split of the column groups over the persistent grid): EVERY one of the
+    6.4e9 outputs against the oracle.  The arrays are streamed back in column blocks (columns are
+    independent, so the oracle runs block by block); the sampled-column tests cannot see a mistake that
+    touches only the few columns at a workgroup's chunk boundary, this one does."""
+    from paper_2002_01119_amd import placement as plc
+    wl = inp.workload(5)
+    n, d = wl.n, wl.d
+    specs = [("X", torch.float32), ("Y", torch.float32), ("G", torch.bfloat16)]
+    total_mem = torch.cuda.mem_get_info()[1]
+    views, pool, pitch = plc.pitched_layout(n, d, specs, int(0.65 * total_mem), "cuda:0", settle=False)
+    X = inp.fill_normal_rows_(views["X"], wl.sigma_x, wl.seed_x)
+    G = inp.fill_normal_rows_(views["G"], wl.sigma_g, wl.seed_g)
+    Y = views["Y"]
+    Y.fill_(float("nan"))
+    nbr, w = psgd.build_mixing(wl.topology, n, wl.seed_perm, 3)
+    onbr, ow = orc.neighbour_table(wl.topology, n, wl.seed_perm, 3)
+    assert np.array_equal(nbr, onbr) and np.array_equal(w.view(np.uint32), ow.view(np.uint32))
+    T = orc.densify(nbr, w)
+    cd = torch.zeros(1, dtype=torch.float64, device="cuda:0")
+    psgd.mix_step(X, Y, G, dev(nbr), dev(w), wl.lr, cdist_out=cd)
+    torch.cuda.synchronize()
+    assert psgd.device_status() == 0
+    block = 2_000_000
+    max_err = max_out = 0.0
+    err2 = out2 = 0.0
+    c_sum = 0.0
+    for lo in range(0, d, block):
+        hi = min(lo + block, d)
+        Xb = X[:, lo:hi].contiguous().cpu().numpy()
+        Gb = inp.bf16_tensor_bits(G[:, lo:hi])
+        Yb = Y[:, lo:hi].contiguous().cpu().numpy()
+        want = orc.mix_step(Xb, Gb, T, wl.lr)
+        diff = Yb - want                                   # fp32 - fp64 -> fp64; NaN if an output was never written
+        e = float(np.abs(diff).max())
+        assert e == e, "unwritten output in columns %d..%d" % (lo, hi)
+        max_err = max(max_err, e)
+        max_out = max(max_out, float(np.abs(want).max()))
+        err2 += float((diff * diff).sum())
+        out2 += float((want * want).sum())
+        c_sum += orc.consensus_dist(Yb)                    # columns are independent: the distance adds up
+        # every block by itself already meets the bar against the magnitudes seen so far
+        assert max_err <= REL * max_out, "columns %d..%d: err %.3g vs %.3g" % (lo, hi, max_err, max_out)
+    assert max_err <= REL * max_out
+    assert math.sqrt(err2) <= REL * math.sqrt(out2)
+    assert abs(cd.item() - c_sum) <= REL * c_sum
+    del views, pool, X, Y, G
+    torch.cuda.empty_cache()
+
+
 def test_cfg5_dense_layout_full_size(psgd):
     """The same workload as plain dense tensors (the entry points the baseline names), 4 steps."""
     wl = inp.workload(5)

@@ -268,3 +268,21 @@ def test_host_calls_are_thread_safe_and_errors_are_per_thread():
         t.join()
     assert all(results[k] for k in range(4))
     assert all(errors[k] is None for k in range(4)), errors
+
+
+def test_launch_arithmetic_covers_every_column_group_once_and_clamps_grids(tmp_path):
+    """The persistent-grid arithmetic of the launchers (csrc/psgd_internal.h), compiled for the CPU: every
+    column group has exactly one owner, chunks start on 256-byte boundaries, and no grid exceeds the
+    partials buffer for any compute-unit count."""
+    import shutil
+    import subprocess
+    gxx = shutil.which("g++") or shutil.which("c++")
+    if gxx is None:
+        pytest.skip("no host C++ compiler")
+    exe = str(tmp_path / "launch_plan_check")
+    subprocess.run([gxx, "-std=c++17", "-O1", "-Wall", "-Werror",
+                    "-I", os.path.join(ROOT, "paper_2002_01119_amd", "csrc"),
+                    os.path.join(ROOT, "tests", "launch_plan_check.cpp"), "-o", exe], check=True)
+    r = subprocess.run([exe], capture_output=True, text=True)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "launch plan ok" in r.stdout
