@@ -43,6 +43,7 @@ enum {
 enum { PSGD_DEG = 3 };       /* slots per table row: self, left, right */
 enum { PSGD_MAX_N = 512 };   /* largest learner count the kernels stage in LDS */
 enum { PSGD_MAX_DEG = 32, PSGD_MAX_TABLE = 4096 };  /* psgd_mix_step_deg: slots per row, n * deg */
+enum { PSGD_STATIC_SLOTS = 1024 };  /* psgd_mix_step_cd_static: partial sums its fixed scratch array holds */
 
 typedef enum {
     PSGD_OK = 0,
@@ -179,6 +180,28 @@ int psgd_mix_step_ex(const float* X, int64_t ldx, float* X_out, int64_t ldo,
                      const void* G, int64_t ldg, int g_is_bf16,
                      const int32_t* nbr, const float* w,
                      int n, int64_t d, float lr, int delay_mode, double* cdist_out, void* stream);
+
+/*
+ * psgd_mix_step_cd_static - psgd_mix_step_ex with a distance output, for callers that cannot
+ * allocate device memory: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same kernels and the same results as psgd_mix_step_ex
+ * with cdist_out (which is required here); the one difference is where the per-workgroup
+ * partial sums of the distance live: in a fixed array of PSGD_STATIC_SLOTS doubles (8 KB) that
+ * is part of the library's device image, one copy per GPU, held until the process ends.  The
+ * call makes no hipMalloc / hipFree and creates no event or stream.
+ *
+ * Limit: a launch uses one partial per persistent workgroup (at most 4 per compute unit; 1024
+ * on MI355X).  If the device would need more than PSGD_STATIC_SLOTS the call fails with
+ * PSGD_EINVAL and launches nothing.  n, d and the pitches are limited as in psgd_mix_step_ex.
+ * Every call on a GPU uses that GPU's one array, which keeps the previous call's partials (each
+ * launch overwrites the slots it reads, so nothing needs clearing).  Calls that overlap in time
+ * on one GPU (two streams, or two graphs launched side by side) race on it: the caller orders
+ * them.  It does not share the buffer of psgd_mix_step_cd / psgd_consensus_dist_async.
+ */
+int psgd_mix_step_cd_static(const float* X, int64_t ldx, float* X_out, int64_t ldo,
+                            const void* G, int64_t ldg, int g_is_bf16,
+                            const int32_t* nbr, const float* w,
+                            int n, int64_t d, float lr, int delay_mode, double* cdist_out, void* stream);
 
 /*
  * psgd_mix_step_deg - the step of Sec. 2, Eq. 2 for any sparse mixing matrix given as a table

@@ -26,6 +26,11 @@
 #include "psgd.h"
 #include "psgd_internal.h"
 
+// Partial sums of psgd_mix_step_cd_static, the entry point for callers that cannot allocate: one double
+// per persistent workgroup.  Every GPU holds its own copy of this array at its own address; host code
+// never uses the name as a pointer, only the address hipGetSymbolAddress returns for the current device.
+static __device__ __align__(256) double scratch[PSGD_STATIC_SLOTS];
+
 namespace psgd {
 namespace {
 
@@ -834,6 +839,7 @@ struct DeviceInfo {
     hipEvent_t partials_idle = nullptr;  // recorded behind the last kernel that read `partials`
     hipStream_t partials_stream = nullptr;  // the stream that event was recorded on
     bool partials_used = false;
+    double* static_partials = nullptr;  // device address of ::scratch on this GPU (psgd_mix_step_cd_static)
 };
 constexpr int kMaxDevices = 64;
 DeviceInfo g_dev[kMaxDevices];
@@ -909,6 +915,20 @@ int release_partials(DeviceInfo* di, hipStream_t s) {
     if (e != hipSuccess) return hip_fail(e, "hipEventRecord(partials)");
     di->partials_stream = s;
     di->partials_used = true;
+    return PSGD_OK;
+}
+
+// Device address of the static scratch array on the current GPU, looked up once per device.
+int static_partials(DeviceInfo* di, double** out) {
+    std::lock_guard<std::mutex> lock(g_dev_mutex);
+    if (!di->static_partials) {
+        double* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        if (!ptr) return fail(PSGD_EHIP, "hipGetSymbolAddress(scratch) returned a null address");
+        di->static_partials = ptr;
+    }
+    *out = di->static_partials;
     return PSGD_OK;
 }
 
@@ -1020,7 +1040,7 @@ int launch_mix(const DeviceInfo& di, bool big, size_t lds_bytes, hipStream_t s, 
 template <typename GT>
 int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, int64_t ldo, const GT* G, int64_t ldg,
                   const int32_t* nbr, const float* w, int n, int64_t d, float lr, int delay_mode, bool want_cd,
-                  double* cd_out, void* stream, int deg = 3) {
+                  double* cd_out, void* stream, int deg = 3, bool no_alloc = false) {
     clear_error();
     if (!X || !X_out || !G || !nbr || !w || (want_cd && !cd_out)) return fail(PSGD_EINVAL, "%s: null pointer", name);
     if (n < 1 || n > PSGD_MAX_N) return fail(PSGD_EINVAL, "%s: n=%d outside 1..%d", name, n, (int)PSGD_MAX_N);
@@ -1053,15 +1073,24 @@ int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
     DeviceInfo* di = nullptr;
     if (d == 0 && !want_cd) return PSGD_OK;
     if (int rc = device_info(&di)) return rc;
+    // Where the per-workgroup partial sums of the distance go: the library's own buffer (allocated on first
+    // use, shared by every call on the device, streams serialised), or the static array of the entry point
+    // that may not allocate (no serialisation: that would need an event).
     double* partials = nullptr;
-    const int slots = kMaxGrid;
-    if (want_cd)
-        if (int rc = acquire_partials(di, s, &partials)) return rc;
+    int slots = kMaxGrid;
+    if (want_cd) {
+        if (no_alloc) {
+            if (int rc = static_partials(di, &partials)) return rc;
+            slots = PSGD_STATIC_SLOTS;
+        } else if (int rc = acquire_partials(di, s, &partials)) {
+            return rc;
+        }
+    }
     if (d == 0) {
         hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, partials, 0, cd_out);
         const hipError_t e0 = hipGetLastError();
         if (e0 != hipSuccess) return hip_fail(e0, "consensus_final_kernel");
-        return release_partials(di, s);
+        return no_alloc ? PSGD_OK : release_partials(di, s);
     }
     // 128-bit path needs every row start 16-byte aligned (8-byte for bf16 gradients).
     const bool vec4 = (d % 4 == 0) && (ldx % 4 == 0) && (ldo % 4 == 0) && (ldg % 4 == 0) && aligned_to(X, 16) &&
@@ -1122,14 +1151,16 @@ int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
         grid = launch_mix<1, GT, true>(*di, big, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials, slots);
     else
         grid = launch_mix<1, GT, false>(*di, big, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials, slots);
-    if (grid < 0) return fail(PSGD_EINVAL, "%s: the launch needs %d partial sums", name, -grid);
+    if (grid < 0)
+        return fail(PSGD_EINVAL, "%s: this launch needs %d partial sums, the static scratch holds %d (PSGD_STATIC_SLOTS)",
+                    name, -grid, (int)PSGD_STATIC_SLOTS);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, name);
     if (want_cd) {
         hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, s, partials, grid, cd_out);
         e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e, "consensus_final_kernel");
-        return release_partials(di, s);
+        if (!no_alloc) return release_partials(di, s);
     }
     return PSGD_OK;
 }
@@ -1299,6 +1330,21 @@ int psgd_mix_step_ex(const float* X, int64_t ldx, float* X_out, int64_t ldo, con
                                              stream);
     return psgd::mix_step_impl<float>("psgd_mix_step_ex", X, ldx, X_out, ldo, static_cast<const float*>(G), ldg, nbr,
                                       w, n, d, lr, delay_mode, cdist_out != nullptr, cdist_out, stream);
+}
+
+int psgd_mix_step_cd_static(const float* X, int64_t ldx, float* X_out, int64_t ldo, const void* G, int64_t ldg,
+                            int g_is_bf16, const int32_t* nbr, const float* w, int n, int64_t d, float lr,
+                            int delay_mode, double* cdist_out, void* stream) {
+    if (g_is_bf16 != 0 && g_is_bf16 != 1) {
+        psgd::clear_error();
+        return psgd::fail(PSGD_EINVAL, "psgd_mix_step_cd_static: g_is_bf16=%d", g_is_bf16);
+    }
+    if (g_is_bf16)
+        return psgd::mix_step_impl<uint16_t>("psgd_mix_step_cd_static", X, ldx, X_out, ldo,
+                                             static_cast<const uint16_t*>(G), ldg, nbr, w, n, d, lr, delay_mode, true,
+                                             cdist_out, stream, 3, true);
+    return psgd::mix_step_impl<float>("psgd_mix_step_cd_static", X, ldx, X_out, ldo, static_cast<const float*>(G), ldg,
+                                      nbr, w, n, d, lr, delay_mode, true, cdist_out, stream, 3, true);
 }
 
 int psgd_mix_step_deg(const float* X, int64_t ldx, float* X_out, int64_t ldo, const void* G, int64_t ldg, int g_is_bf16,

@@ -15,6 +15,7 @@ TOPO_RAND_RING = 1
 TOPO_FULL = 2
 DEG = 3
 MAX_N = 512
+STATIC_SLOTS = 1024
 
 OK, EINVAL, EALIAS, EALIGN, EHIP = 0, -1, -2, -3, -4
 
@@ -23,7 +24,7 @@ _lib = None
 
 EXPORTS = (
     "psgd_build_mixing", "psgd_build_mixing_device", "psgd_mix_step", "psgd_mix_step_bf16g", "psgd_mix_step_cd",
-    "psgd_mix_step_cd_bf16g", "psgd_mix_step_ex", "psgd_mix_step_deg", "psgd_mix_full", "psgd_consensus_dist", "psgd_consensus_dist_ex",
+    "psgd_mix_step_cd_bf16g", "psgd_mix_step_ex", "psgd_mix_step_cd_static", "psgd_mix_step_deg", "psgd_mix_full", "psgd_consensus_dist", "psgd_consensus_dist_ex",
     "psgd_consensus_dist_async", "psgd_synth_grad", "psgd_synth_grad_ex", "psgd_device_status", "psgd_last_error",
     "psgd_version",
 )
@@ -66,6 +67,8 @@ def load(reload=False):
     lib.psgd_mix_step_ex.restype = ctypes.c_int
     lib.psgd_mix_step_ex.argtypes = [vp, ctypes.c_int64, vp, ctypes.c_int64, vp, ctypes.c_int64, ctypes.c_int,
                                      vp, vp, ctypes.c_int, ctypes.c_int64, ctypes.c_float, ctypes.c_int, vp, vp]
+    lib.psgd_mix_step_cd_static.restype = ctypes.c_int
+    lib.psgd_mix_step_cd_static.argtypes = list(lib.psgd_mix_step_ex.argtypes)
     lib.psgd_mix_step_deg.restype = ctypes.c_int
     lib.psgd_mix_step_deg.argtypes = [vp, ctypes.c_int64, vp, ctypes.c_int64, vp, ctypes.c_int64, ctypes.c_int,
                                       vp, vp, ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_float,
@@ -215,6 +218,34 @@ def mix_step(X, X_out, G, nbr, w, lr, delay_mode=0, stream=None, cdist_out=None)
         fn = lib.psgd_mix_step_cd_bf16g if bf16 else lib.psgd_mix_step_cd
         _check(fn(X.data_ptr(), X_out.data_ptr(), G.data_ptr(), nbr.data_ptr(), w.data_ptr(), n, d,
                   float(lr), int(delay_mode), cd_ptr, sh))
+
+
+def mix_step_cd_static(X, X_out, G, nbr, w, lr, cdist_out, delay_mode=0, stream=None):
+    """psgd_mix_step_cd_static: the fused step + distance of mix_step (3-slot tables, any row pitch) through
+    the entry point that allocates nothing."""
+    import torch
+    n, d, ldx = _rows_cols_pitch(X)
+    no, do, ldo = _rows_cols_pitch(X_out)
+    ng, dg, ldg = _rows_cols_pitch(G)
+    if (no, do) != (n, d) or (ng, dg) != (n, d):
+        raise ValueError("X, X_out and G must have one shape")
+    if X.dtype != torch.float32 or X_out.dtype != torch.float32:
+        raise ValueError("X and X_out must be float32")
+    if nbr.dtype != torch.int32 or w.dtype != torch.float32 or nbr.numel() != DEG * n or w.numel() != DEG * n \
+            or not nbr.is_contiguous() or not w.is_contiguous():
+        raise ValueError("nbr must be int32 [n,3] and w float32 [n,3], contiguous")
+    if G.dtype == torch.float32:
+        bf16 = 0
+    elif G.dtype in (torch.bfloat16, torch.int16, torch.uint16):
+        bf16 = 1
+    else:
+        raise ValueError("G must be float32 or bfloat16 bit patterns")
+    if cdist_out is None or cdist_out.dtype != torch.float64 or cdist_out.numel() < 1 or cdist_out.device != X.device:
+        raise ValueError("cdist_out must be a float64 device tensor")
+    _on_current_device(X, X_out, G, nbr, w, cdist_out)
+    _check(load().psgd_mix_step_cd_static(X.data_ptr(), ldx, X_out.data_ptr(), ldo, G.data_ptr(), ldg, bf16,
+                                          nbr.data_ptr(), w.data_ptr(), n, d, float(lr), int(delay_mode),
+                                          cdist_out.data_ptr(), _stream_handle(stream)))
 
 
 def mix_full(X, X_out, G, lr, delay_mode=0, stream=None, cdist_out=None):
