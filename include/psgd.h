@@ -43,7 +43,7 @@ enum {
 enum { PSGD_DEG = 3 };       /* slots per table row: self, left, right */
 enum { PSGD_MAX_N = 512 };   /* largest learner count the kernels stage in LDS */
 enum { PSGD_MAX_DEG = 32, PSGD_MAX_TABLE = 4096 };  /* psgd_mix_step_deg: slots per row, n * deg */
-enum { PSGD_STATIC_SLOTS = 1024 };  /* psgd_mix_step_cd_static: partial sums its fixed scratch array holds */
+enum { PSGD_STATIC_SLOTS = 2048 };  /* psgd_mix_step_cd_static: partial sums its fixed scratch array holds */
 
 typedef enum {
     PSGD_OK = 0,
@@ -113,7 +113,10 @@ int psgd_build_mixing_device(int topology, int n, uint64_t seed, uint64_t* step_
  * Per element, in fp32 and in this order: acc = w0 * x_self; acc = fma(w1, x_left, acc);
  * acc = fma(w2, x_right, acc); out = fma(-lr, g, acc).
  *
- * Enqueues one kernel on `stream`; returns without waiting.  Errors: PSGD_EINVAL;
+ * Enqueues two kernels on `stream` and returns without waiting: the table lives in device
+ * memory, so only the device can tell whether it is one ring (every table of Sec. 3 is) or a
+ * general 3-slot table; the ring-walk kernel and the tiled kernel both classify it, and the one
+ * the table does not belong to exits at once.  Errors: PSGD_EINVAL;
  * PSGD_EALIAS (X_out partially overlaps X, X_out overlaps G, or X_out == X with
  * delay_mode 1); PSGD_EALIGN (X, X_out, G not 4-byte aligned); PSGD_EHIP.  A table entry
  * outside [0, n) cannot be seen by the host: the kernel then writes nothing and raises the
@@ -186,13 +189,14 @@ int psgd_mix_step_ex(const float* X, int64_t ldx, float* X_out, int64_t ldo,
  * allocate device memory: code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc.  Same arguments, same kernels and the same results as psgd_mix_step_ex
  * with cdist_out (which is required here); the one difference is where the per-workgroup
- * partial sums of the distance live: in a fixed array of PSGD_STATIC_SLOTS doubles (8 KB) that
+ * partial sums of the distance live: in a fixed array of PSGD_STATIC_SLOTS doubles (16 KB) that
  * is part of the library's device image, one copy per GPU, held until the process ends.  The
  * call makes no hipMalloc / hipFree and creates no event or stream.
  *
- * Limit: a launch uses one partial per persistent workgroup (at most 4 per compute unit; 1024
- * on MI355X).  If the device would need more than PSGD_STATIC_SLOTS the call fails with
- * PSGD_EINVAL and launches nothing.  n, d and the pitches are limited as in psgd_mix_step_ex.
+ * Limit: a launch uses one partial per persistent workgroup of its two kernels (the ring walk:
+ * at most 4 per compute unit, 1024 on MI355X; the tiled kernel behind it takes what is left).
+ * If the ring walk alone would need PSGD_STATIC_SLOTS or more the call fails with PSGD_EINVAL
+ * and launches nothing.  n, d and the pitches are limited as in psgd_mix_step_ex.
  * Every call on a GPU uses that GPU's one array, which keeps the previous call's partials (each
  * launch overwrites the slots it reads, so nothing needs clearing).  Calls that overlap in time
  * on one GPU (two streams, or two graphs launched side by side) race on it: the caller orders
@@ -211,7 +215,7 @@ int psgd_mix_step_cd_static(const float* X, int64_t ldx, float* X_out, int64_t l
  * remedy of the prior work the paper cites in Sec. 7).  1 <= deg <= PSGD_MAX_DEG and
  * n * deg <= PSGD_MAX_TABLE.  Per element: acc = w0 * x0; acc = fma(w_s, x_s, acc) for
  * s = 1..deg-1 in table order; out = fma(-lr, g, acc).  deg = 3 is psgd_mix_step_ex (ring
- * tables then take the register walk); other degrees always stage an [n x columns] tile in
+ * tables then take the register walk); other degrees always stage [n x columns] tiles in
  * LDS.  Everything else (pitches, gradient type, in-place rule, cdist_out gathered in the same
  * pass, errors) is as in psgd_mix_step_ex.
  */
@@ -270,6 +274,23 @@ int psgd_synth_grad(const float* X_prev, const float* noise, float* G,
 /* psgd_synth_grad_ex - the same for [n, d] arrays whose rows are ld* (>= d) elements apart. */
 int psgd_synth_grad_ex(const float* X_prev, int64_t ldx, const float* noise, int64_t ldn,
                        float* G, int64_t ldg, int n, int64_t d, float c, void* stream);
+
+/*
+ * psgd_reference_stream - measurement support, not a step of the method: the memory traffic of
+ * the fused step with the mixing taken out, issued exactly as the step's kernel issues it (a lane
+ * per 128-bit column group walking the n rows, workgroups sweeping the rows in lockstep batches,
+ * the same persistent grid).  The rate it reaches on a given placement of the arrays is the
+ * ceiling the step is compared with in the benchmark.
+ *
+ *   kind 0  read X and G, write nothing          (4 + 2 or 4 + 4 bytes per element)
+ *   kind 1  write X_out[i, j] = a, read nothing   (4 bytes per element)
+ *   kind 2  X_out = X + a * G                     (the step's 4 + 2 + 4 or 4 + 4 + 4 bytes)
+ * Arguments as in psgd_mix_step_ex (all three arrays must be valid for every kind); d and the
+ * pitches must be multiples of 4 and the rows 128-bit aligned (PSGD_EALIGN otherwise); X_out
+ * must not overlap X or G for kinds 1 and 2.  Enqueues one kernel on `stream`.
+ */
+int psgd_reference_stream(int kind, const float* X, int64_t ldx, float* X_out, int64_t ldo,
+                          const void* G, int64_t ldg, int g_is_bf16, int n, int64_t d, float a, void* stream);
 
 /*
  * psgd_device_status - waits for the current device, then returns the sticky flag word that

@@ -29,6 +29,8 @@ Pins (tests/test_oracle_pins.py, all CPU):
                          mutants are caught
   mix_step               element-by-element triple loop, asymmetric shift matrix,
                          n = 1 reduces to Eq. 1, T_u gives the column mean, mean recurrence
+  sparse_mix_step (C)    typed-out asymmetric example; equals mix_step(densify(table)) on random
+                         asymmetric and ring tables, fp32 and bf16 gradients, any thread count
   consensus_dist         closed forms (equal rows -> 0; X[i,j] = i -> d n (n^2-1)/12),
                          contraction bound rho^2 of Eq. 5
   synth_grad / d1d_trajectory   reduce to the undelayed run when the X-dependent term is
@@ -274,3 +276,69 @@ def d1d_trajectory(X0, noises, tables, lr, c):
         X_prev = Xs[-1]
         Xs.append(X_next)
     return Xs
+
+
+# --------------------------------------------------------------------------------------
+# Sparse form of the update in plain C (psgd_sparse_oracle.c): the same result as mix_step with the
+# densified table, computed as the gather-add it is.  Used as the CPU baseline of the benchmark (a dense
+# matrix product is an unfairly slow way to apply three neighbours) and pinned against mix_step.
+# --------------------------------------------------------------------------------------
+_SPARSE_LIB = None
+
+
+def build_sparse_lib(force=False):
+    """Compile psgd_sparse_oracle.c with the host C compiler (gcc -O2 -fopenmp) next to its source."""
+    import os
+    import subprocess
+    here = os.path.dirname(os.path.abspath(__file__))
+    src = os.path.join(here, "psgd_sparse_oracle.c")
+    lib = os.path.join(here, "libpsgd_sparse_oracle.so")
+    if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(src):
+        tmp = lib + ".%d.tmp" % os.getpid()
+        subprocess.run([os.environ.get("CC", "gcc"), "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-Wall",
+                        src, "-o", tmp], check=True)
+        os.replace(tmp, lib)
+    return lib
+
+
+def _sparse_lib():
+    global _SPARSE_LIB
+    if _SPARSE_LIB is None:
+        import ctypes
+        lib = ctypes.CDLL(build_sparse_lib())
+        vp = ctypes.c_void_p
+        lib.psgd_oracle_sparse_step.restype = None
+        lib.psgd_oracle_sparse_step.argtypes = [vp, vp, ctypes.c_int, vp, vp, ctypes.c_int, ctypes.c_int,
+                                                ctypes.c_int64, ctypes.c_float, vp, ctypes.c_int]
+        lib.psgd_oracle_consensus.restype = ctypes.c_double
+        lib.psgd_oracle_consensus.argtypes = [vp, ctypes.c_int, ctypes.c_int64, ctypes.c_int]
+        _SPARSE_LIB = lib
+    return _SPARSE_LIB
+
+
+def sparse_mix_step(X, G, nbr, w, lr, threads=1):
+    """out[i] = sum_s w[i,s] X[nbr[i,s]] - lr G[i] (Sec. 2, Eq. 2; table row i = column i of T), float64.
+
+    X: [n, d] fp32; G: [n, d] fp32 or bf16 bit patterns (uint16); nbr int32 [n, deg]; w fp32 [n, deg]."""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    G = np.ascontiguousarray(G)
+    if G.dtype not in (np.float32, np.uint16):
+        raise ValueError("G must be float32 or uint16 bf16 bit patterns")
+    nbr = np.ascontiguousarray(nbr, dtype=np.int32)
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    n, d = X.shape
+    if G.shape != (n, d) or nbr.shape != w.shape or nbr.shape[0] != n:
+        raise ValueError("shape mismatch")
+    if nbr.size and (nbr.min() < 0 or nbr.max() >= n):
+        raise ValueError("table entry outside [0, n)")
+    out = np.empty((n, d), dtype=np.float64)
+    _sparse_lib().psgd_oracle_sparse_step(X.ctypes.data, G.ctypes.data, int(G.dtype == np.uint16), nbr.ctypes.data,
+                                          w.ctypes.data, int(nbr.shape[1]), n, d, float(np.float32(lr)),
+                                          out.ctypes.data, int(threads))
+    return out
+
+
+def sparse_consensus_dist(X64, threads=1):
+    """Two-pass consensus distance of a float64 [n, d] array, in C (same definition as consensus_dist)."""
+    X64 = np.ascontiguousarray(X64, dtype=np.float64)
+    return float(_sparse_lib().psgd_oracle_consensus(X64.ctypes.data, X64.shape[0], X64.shape[1], int(threads)))

@@ -37,13 +37,15 @@ namespace {
 constexpr int kThreads = 256;        // 4 wavefronts of 64 lanes
 constexpr int kRingThreads = 768;    // workgroup of the step kernels on long rows (12 wavefronts in lockstep, one per CU;
                                      // 1024 lanes would leave the fused distance too few registers)
-constexpr int kTileBytes = 32 * 1024;  // LDS budget of the tiled path per workgroup
+constexpr int kTileThreads = 512;    // workgroup of the tiled path on long rows: 8 wavefronts, alone on its CU, so each may
+                                     // hold 256 registers (the next tile's rows travel through them)
 constexpr int kUnroll = 8;           // rows whose loads are in flight together per lane
-constexpr int kTileUnroll = 4;     // rows whose loads a lane of the tiled path keeps in flight (8 would cost a
-                                   // resident workgroup per CU in registers, which this path needs more)
 using plan::kMaxGrid;                // upper bound on persistent workgroups (partials buffer sizing)
 constexpr int kGridPerCu = 4;        // persistent workgroups per compute unit (16 waves per CU)
-constexpr size_t kDegLdsLimit = 96 * 1024;  // LDS a workgroup of the degree-K kernel may ask for (160 KB per CU)
+// LDS a workgroup may ask for: a compute unit has 160 KB.  The large lockstep workgroup is alone on its CU
+// and may take nearly all of it; the small one leaves room for four per CU unless the table needs more.
+constexpr size_t kLdsCapLarge = 160 * 1024 - 1024;
+constexpr size_t kLdsCapSmall = 40 * 1024 - 256;
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -86,6 +88,39 @@ __device__ __forceinline__ f32x4 ld_g(const uint16_t* p, Cols<4>) {
                    __uint_as_float(b.y << 16), __uint_as_float(b.y & 0xFFFF0000u)};
 }
 
+// A gradient group as it arrives from memory, widened only where it is used: a value that is converted right
+// after its load would make the wavefront wait for that load (and every earlier one) on the spot, which defeats
+// loads that are issued early to travel during other work; bf16 groups also take half the registers this way.
+template <typename GT, int VEC> struct RawG;
+template <> struct RawG<float, 4> { typedef f32x4 T; };
+template <> struct RawG<float, 1> { typedef float T; };
+template <> struct RawG<uint16_t, 4> { typedef u32x2 T; };
+template <> struct RawG<uint16_t, 1> { typedef uint16_t T; };
+__device__ __forceinline__ f32x4 ld_g_raw(const float* p, Cols<4> c) { return ld_x(p, c); }
+__device__ __forceinline__ float ld_g_raw(const float* p, Cols<1> c) { return ld_x(p, c); }
+__device__ __forceinline__ u32x2 ld_g_raw(const uint16_t* p, Cols<4>) {
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+}
+__device__ __forceinline__ uint16_t ld_g_raw(const uint16_t* p, Cols<1>) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ f32x4 widen_g(f32x4 v) { return v; }
+__device__ __forceinline__ float widen_g(float v) { return v; }
+__device__ __forceinline__ f32x4 widen_g(u32x2 b) {
+    return (f32x4){__uint_as_float(b.x << 16), __uint_as_float(b.x & 0xFFFF0000u),
+                   __uint_as_float(b.y << 16), __uint_as_float(b.y & 0xFFFF0000u)};
+}
+__device__ __forceinline__ float widen_g(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// Two barriers that are lighter than __syncthreads(), which also waits until every global load and store the
+// wavefront has issued is complete.  That wait is exactly what the step kernels must avoid: their loads are
+// issued early to travel during other work, and their stores need never be waited for.
+//   lockstep_barrier: keeps the workgroup's wavefronts on the same batch of rows; no data passes between them.
+//   lds_barrier: the wavefront's own LDS reads and writes are complete (its global ones may still travel), then
+//   the barrier: LDS written before it by any wavefront is read after it by any other.
+__device__ __forceinline__ void lockstep_barrier() { __builtin_amdgcn_s_barrier(); }
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // One output group.  The operation order is part of the boundary's contract.
 template <typename V>
 __device__ __forceinline__ V mix_one(float w0, float w1, float w2, V self, V left, V right,
@@ -109,36 +144,32 @@ struct __attribute__((aligned(16))) RingEnt {
     float w0, w1, w2;
 };
 
-// LDS carve-up (dynamic, sized by the launcher):
-//   RingEnt ring[n] | int nbr[3n] | float w[3n] | scratch (ranking arrays or the data tile)
-// Tables with another slot count never take the ring walk; they keep only
-//   float w[deg n] | uint16 nbr16[deg n] | scratch (the data tile)
-// (n <= 512 fits 16 bits; the 2 bytes saved per slot decide whether a fourth workgroup fits a CU).
+// One slot of a table row as the tiled path keeps it in LDS: where the source row starts inside the tile
+// (nbr * lanes-per-row, in column groups) and its weight.
+struct __attribute__((aligned(8))) TileSlot {
+    uint32_t off;
+    float w;
+};
+
+// LDS carve-up of the 3-slot step kernel (dynamic, sized by the launcher):
+//   RingEnt ring[n] | int nbr[3n] | float w[3n] | scratch
+// scratch holds the ranking arrays while the table is classified and, for a table that is not one ring, the
+// tiled path's slot table, tile buffers and merge slots (plan::tile_plan).
 struct Lds {
     RingEnt* ring;
     int* nbr;
-    uint16_t* nbr16;
     float* w;
     char* scratch;
 };
-__host__ __device__ inline size_t lds_table_bytes(int n, int deg = 3) {
-    return deg == 3 ? (size_t)n * (sizeof(RingEnt) + 3 * (sizeof(int) + sizeof(float)))
-                    : (size_t)n * deg * (sizeof(float) + sizeof(uint16_t));
+__host__ __device__ inline size_t lds_table_bytes(int n) {
+    return (((size_t)n * (sizeof(RingEnt) + 3 * (sizeof(int) + sizeof(float)))) + 15) & ~(size_t)15;
 }
-__device__ __forceinline__ Lds carve(char* base, int n, int deg = 3) {
+__device__ __forceinline__ Lds carve(char* base, int n) {
     Lds l;
     l.ring = reinterpret_cast<RingEnt*>(base);
-    if (deg == 3) {
-        l.nbr = reinterpret_cast<int*>(base + (size_t)n * sizeof(RingEnt));
-        l.w = reinterpret_cast<float*>(l.nbr + 3 * n);
-        l.nbr16 = nullptr;
-    } else {
-        l.nbr = nullptr;
-        l.w = reinterpret_cast<float*>(base);
-        l.nbr16 = reinterpret_cast<uint16_t*>(l.w + deg * n);
-    }
-    // keep the scratch 16-byte aligned
-    l.scratch = base + ((lds_table_bytes(n, deg) + 15) & ~(size_t)15);
+    l.nbr = reinterpret_cast<int*>(base + (size_t)n * sizeof(RingEnt));
+    l.w = reinterpret_cast<float*>(l.nbr + 3 * n);
+    l.scratch = base + lds_table_bytes(n);   // 16-byte aligned
     return l;
 }
 
@@ -333,7 +364,7 @@ __device__ __forceinline__ void ring_walk(const float* xc, float* oc, const GT* 
     // Whole batches: positions p .. p+U-1, whose right neighbours p+1 .. p+U are all fresh
     // loads (none of them is position n-1 or the wrap to position 0).
     for (; p + kUnroll <= n - 2; p += kUnroll) {
-        __syncthreads();
+        lockstep_barrier();
         RingEnt e[kUnroll];
         V xs[kUnroll], gs[kUnroll];
 #pragma unroll
@@ -381,140 +412,363 @@ __device__ __forceinline__ void ring_walk(const float* xc, float* oc, const GT* 
 }
 
 // ---------------------------------------------------------------------------------------
-// Tiled path for tables that are not a single ring.  The workgroup's 256 lanes form
-// (256 / lpr) row groups of lpr lanes; a tile is n rows by lpr column groups.
-// ---------------------------------------------------------------------------------------
-// Extra LDS of the tiled path when it also gathers the consensus statistics: one partial
-// column sum per wavefront and column.
-__host__ __device__ inline size_t tile_cd_bytes(int lpr, int vec, int threads = kThreads) {
-    return 8 + (size_t)(threads / 64) * lpr * vec * sizeof(double);
-}
-
-// One output group from the tile: slots in table order, acc = w0 * x0, then one fma per
-// further slot, then the gradient term (for 3 slots this is exactly mix_one's order).
-// 16-bit tables (the degree-K kernel's) hold nbr * lpr, the tile offset of the row, 32-bit ones nbr.
-template <typename V, typename IT>
-__device__ __forceinline__ V mix_slots(const V* tile, const IT* nbr, const float* w, int deg, int lpr, int lane, V g,
-                                       float neg_lr) {
-    constexpr bool kPremul = sizeof(IT) == 2;
-    const int scale = kPremul ? 1 : lpr;
-    V acc = tile[nbr[0] * scale + lane] * w[0];
-    for (int s = 1; s < deg; ++s) acc = vfma(w[s], tile[nbr[s] * scale + lane], acc);
-    return vfma(neg_lr, g, acc);
-}
-
-// FULL states that every lane owns a whole number of batches (n is a multiple of kTileUnroll row
-// groups), which removes the per-row guards.
-// A lane's rows are rg, rg + nrg, ...; they are handled kTileUnroll at a time: that many loads
-// are in flight together, and the table look-ups and tile reads of that many rows (independent
-// chains of two dependent LDS reads per slot) interleave instead of queueing behind each other.
+// Tiled path for tables that are not a single ring (any number of slots per row).
 //
-// With CD the distance of the outputs is gathered in the same pass.  The rows of one column
-// group are spread over the row groups, so all of them measure against ONE pivot, the output
-// of row 0, which every row group computes for itself (bit-identical: same tile, same table,
-// same gradient bits; the extra read of G's row 0 is served by the cache).  The squares then
-// add up lane by lane and only the plain sums need merging per column, through LDS.
-template <int VEC, typename GT, bool CD, typename IT, bool FULL = false, int T = kThreads>
-__device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ G, const Lds& l, const IT* nbr_tab,
-                            int n, Pitch ld, int64_t ncg, float neg_lr, int lpr, double inv_n, int deg = 3) {
-    typedef typename Cols<VEC>::T V;
-    const Cols<VEC> tag{};
-    constexpr int U = kTileUnroll;
-    V* tile = reinterpret_cast<V*>(l.scratch);
-    // [T / 64 wavefronts][lpr][VEC] doubles (CD only), 8-byte aligned behind the tile.  The offset is
-    // rounded, not the pointer: a pointer that has been through an integer loses its LDS
-    // address space and every access through it becomes a (slow) generic-address instruction.
-    double* comb = reinterpret_cast<double*>(l.scratch + (((size_t)n * lpr * sizeof(V) + 7) & ~(size_t)7));
-    const int lane = threadIdx.x % lpr, rg = threadIdx.x / lpr, nrg = T / lpr;
-    const int64_t ntiles = (ncg + lpr - 1) / lpr;
-    double total = 0.0;
-    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
-        const int64_t cg = t * lpr + lane;
-        const bool active = cg < ncg;
-        const int64_t col = cg * VEC;
-        // The gradients of the first batch and of row 0 (for the pivot) do not depend on the
-        // tile: requested before the barrier, their latency hides behind the tile's load.
-        V gs[U], g0 = {};
-        if (active) {
-            if (CD) g0 = ld_g(G + col, tag);
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int r = rg + u * nrg;
-                if (FULL || r < n) gs[u] = ld_g(G + (int64_t)r * ld.g + col, tag);
-            }
-            for (int r0 = rg; r0 < n; r0 += U * nrg) {
-                V xs[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int r = r0 + u * nrg;
-                    if (FULL || r < n) xs[u] = ld_x(X + (int64_t)r * ld.x + col, tag);
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int r = r0 + u * nrg;
-                    if (FULL || r < n) tile[r * lpr + lane] = xs[u];
-                }
-            }
-        }
-        __syncthreads();
-        double piv[VEC], a[VEC], sq = 0.0;
+// The workgroup's T lanes form T / lpr row groups of lpr lanes; a tile is n rows by lpr column groups and lives
+// in LDS, so a neighbour read is an LDS read and every X element crosses the HBM interface once.  Lane (rg,
+// lane) produces rows rg, rg + nrg, ... of column group `lane` of the tile.  Two tile buffers alternate: while
+// the rows of tile t are computed from one, the X rows of the workgroup's next tile travel from HBM into
+// registers and are stored into the other at the end of each batch of rows; the gradients of the following
+// batch travel at the same time.  One barrier per tile separates "everyone has finished reading this buffer and
+// writing the other" from the next round.  A tile is complete in LDS before its first output is stored, and
+// different tiles own different columns, so X_out may alias X.
+//
+// Per output the slots are taken in table order, acc = w0 * x0, one fma per further slot, then the gradient
+// term (for 3 slots exactly mix_one's order).  The slot loop is the latency-critical part (a table read, then
+// a tile read that depends on it, per slot): SB rows advance together and two slots per trip, so SB * 2
+// independent chains hide each other's LDS round trips.
+//
+// With CD the distance of the outputs is gathered in the same pass.  The rows of one column group are spread
+// over the row groups, so all of them measure against ONE pivot, the output of row 0, which every row group
+// computes for itself (bit-identical: same tile, same table, same gradient bits).  The squares then add up lane
+// by lane and only the plain sums need merging per column: across the row groups that share a wavefront by
+// shuffles, across wavefronts through one LDS slot each, summed in fixed order.
+// ---------------------------------------------------------------------------------------
+// The large workgroup is alone on its compute unit and may use 256 registers per lane: 8 rows in flight (8
+// wavefronts x 8 rows cover n = 64 at once).  The small one, which serves short rows (launches bound by latency,
+// several workgroups per CU) and shares the 3-slot kernel with the ring walk there, stays frugal.
+template <int T> struct TileShape {
+    static constexpr int RB = T > 256 ? 8 : 2;   // rows per lane and batch
+    static constexpr int SB = T > 256 ? 3 : 2;   // rows whose slot chains advance together (two slots per trip each);
+                                                 // 3 x 3 = the pivot row + 8 rows when the distance is gathered
+};
+
+// Per-lane state of the tiled path that does not change from tile to tile.
+template <int VEC>
+struct TileCtx {
+    const TileSlot* tab;
+    int n, deg, lpr, lane, rg, nrg;
+    int tlane;   // the lane's column inside the tile (lane, or the last valid one for a lane beyond the ragged end)
+    float neg_lr;
+};
+
+// Running sums of the distance for one lane and one tile.
+template <int VEC>
+struct TileStats {
+    double piv[VEC], a[VEC], sq;
+    __device__ __forceinline__ void reset() {
+        sq = 0.0;
 #pragma unroll
         for (int k = 0; k < VEC; ++k) piv[k] = a[k] = 0.0;
-        if (active) {
-            if (CD) pivot_of(mix_slots<V>(tile, nbr_tab, l.w, deg, lpr, lane, g0, neg_lr), piv);
-            for (int r0 = rg; r0 < n; r0 += U * nrg) {
-                if (r0 != rg) {
+    }
+};
+
+// Rows rg + (b RB + u) nrg, u < RB, of the tile in `cur`: mix, subtract the gradient, store, gather.  With CD and
+// `with_pivot` the list starts with one more item, row 0 of the lane's columns with its gradient g0: its output is
+// the pivot the distance sums are taken against (computed, not stored; it rides along with the first rows so that
+// its chain of LDS reads costs no latency of its own).
+//
+// CLAMP: nothing here is conditional except the arithmetic of the distance.  A lane without a row (or without a
+// column group: the caller then points it at the last valid one) repeats the work of the lane that owns the
+// clamped row and column and stores the same bits to the same place.  This is what lets loads that were issued
+// early stay in flight: the compiler counts outstanding memory operations to wait for exactly the ones it
+// needs, and a load or store that may or may not have been issued makes that count unknown, upon which it
+// waits for all of them.
+template <int VEC, bool CD, int RB, int SB, bool CLAMP, typename GR>
+__device__ __forceinline__ void tile_rows(const TileCtx<VEC>& c, const typename Cols<VEC>::T* cur, int b, const GR (&g)[RB],
+                                          GR g0, bool with_pivot, bool active, float* out_col, int64_t ldo,
+                                          TileStats<VEC>& st) {
+    typedef typename Cols<VEC>::T V;
+    constexpr int P = CD ? 1 : 0, ITEMS = RB + P;
 #pragma unroll
-                    for (int u = 0; u < U; ++u) {
-                        const int r = r0 + u * nrg;
-                        if (FULL || r < n) gs[u] = ld_g(G + (int64_t)r * ld.g + col, tag);
-                    }
-                }
+    for (int j0 = 0; j0 < ITEMS; j0 += SB) {
+        const TileSlot* tp[SB];
+        bool ok[SB];
+        int row[SB];
+        V acc[SB];
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int r = r0 + u * nrg;
-                    if (FULL || r < n) {
-                        const V out = mix_slots<V>(tile, nbr_tab + deg * r, l.w + deg * r, deg, lpr, lane, gs[u], neg_lr);
-                        st_x(Xout + (int64_t)r * ld.o + col, out);
-                        if (CD) {
-                            double o[VEC];
-                            pivot_of(out, o);      // widen
+        for (int i = 0; i < SB; ++i) {
+            const int j = j0 + i;
+            const bool piv = CD && j == 0;
+            row[i] = piv ? 0 : c.rg + (b * RB + (j - P)) * c.nrg;
+            ok[i] = j < ITEMS && active && (piv ? with_pivot : row[i] < c.n);
+            if (CLAMP) {
+                if (row[i] > c.n - 1) row[i] = c.n - 1;
+                tp[i] = c.tab + row[i] * c.deg;
+            } else {
+                tp[i] = c.tab + (ok[i] ? row[i] : 0) * c.deg;     // an idle item follows row 0 and stores nothing
+            }
+        }
+        {
+            TileSlot e[SB];
 #pragma unroll
-                            for (int k = 0; k < VEC; ++k) {
-                                const double df = o[k] - piv[k];
-                                a[k] += df;
-                                sq = fma(df, df, sq);
-                            }
+            for (int i = 0; i < SB; ++i) e[i] = tp[i][0];
+#pragma unroll
+            for (int i = 0; i < SB; ++i) acc[i] = cur[e[i].off + c.tlane] * e[i].w;
+        }
+        int s = 1;
+        for (; s + 1 < c.deg; s += 2) {
+            TileSlot e0[SB], e1[SB];
+            V x0[SB], x1[SB];
+#pragma unroll
+            for (int i = 0; i < SB; ++i) {
+                e0[i] = tp[i][s];
+                e1[i] = tp[i][s + 1];
+            }
+#pragma unroll
+            for (int i = 0; i < SB; ++i) {
+                x0[i] = cur[e0[i].off + c.tlane];
+                x1[i] = cur[e1[i].off + c.tlane];
+            }
+#pragma unroll
+            for (int i = 0; i < SB; ++i) {
+                acc[i] = vfma(e0[i].w, x0[i], acc[i]);
+                acc[i] = vfma(e1[i].w, x1[i], acc[i]);
+            }
+        }
+        if (s < c.deg) {
+            TileSlot e[SB];
+#pragma unroll
+            for (int i = 0; i < SB; ++i) e[i] = tp[i][s];
+#pragma unroll
+            for (int i = 0; i < SB; ++i) acc[i] = vfma(e[i].w, cur[e[i].off + c.tlane], acc[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < SB; ++i) {
+            const int j = j0 + i;
+            if (CD && j == 0) {
+                if (CLAMP || ok[i]) pivot_of(vfma(c.neg_lr, widen_g(g0), acc[i]), st.piv);
+            } else if (j < ITEMS) {
+                if (CLAMP || ok[i]) {
+                    const V out = vfma(c.neg_lr, widen_g(g[j - P < 0 ? 0 : j - P]), acc[i]);
+                    st_x(out_col + (int64_t)row[i] * ldo, out);
+                    if (CD && ok[i]) {
+                        double o[VEC];
+                        pivot_of(out, o);      // widen
+#pragma unroll
+                        for (int k = 0; k < VEC; ++k) {
+                            const double df = o[k] - st.piv[k];
+                            st.a[k] += df;
+                            st.sq = fma(df, df, st.sq);
                         }
                     }
                 }
             }
         }
-        if (CD) {
-            // Column sums: first across the row groups that share a wavefront (lanes lpr apart hold
-            // the same columns; the exchange is symmetric, so all of them end with the same bits),
-            // then one slot per wavefront in LDS.
-            const int wl = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    }
+}
+
+// Merge of the column sums at the end of a tile (CD only).  Contains the tile's barrier: when it returns every
+// read of the current buffer and every write of the other one is done.
+template <int VEC, bool CD, int T>
+__device__ __forceinline__ void tile_finish(const TileCtx<VEC>& c, double* comb, bool active, TileStats<VEC>& st,
+                                            double inv_n, double& total) {
+    if (CD) {
+        // first across the row groups that share a wavefront (lanes lpr apart hold the same columns; the exchange
+        // is symmetric, so all of them end with the same bits), then one slot per wavefront in LDS
+        // (rows wider than a wavefront: a row group is whole wavefronts, one slot per row group)
+        const int wl = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
-            for (int k = 0; k < VEC; ++k) {
-                for (int off = lpr; off < 64; off <<= 1) a[k] += __shfl_xor(a[k], off, 64);
-                if (wl < lpr) comb[(size_t)(wave * lpr + wl) * VEC + k] = a[k];
+        for (int k = 0; k < VEC; ++k) {
+            if (c.lpr <= 64) {
+                for (int off = c.lpr; off < 64; off <<= 1) st.a[k] += __shfl_xor(st.a[k], off, 64);
+                if (wl < c.lpr) comb[(size_t)(wave * c.lpr + wl) * VEC + k] = st.a[k];
+            } else {
+                comb[(size_t)(c.rg * c.lpr + c.lane) * VEC + k] = st.a[k];
             }
-            total += sq;
         }
-        // Every read of the tile is done: the next sweep may overwrite it.  (The merge below reads
-        // only `comb`, which is not written again before the barrier that follows the next load.)
-        __syncthreads();
-        if (CD && active && rg == 0) {
+        total += st.sq;
+    }
+    lds_barrier();
+    if (CD) {
+        if (active && c.rg == 0) {
+            const int slots = c.lpr <= 64 ? T / 64 : c.nrg;
 #pragma unroll
             for (int k = 0; k < VEC; ++k) {
                 double at = 0.0;
-#pragma unroll
-                for (int q = 0; q < T / 64; q += 2)
-                    at += comb[(size_t)(q * lpr + lane) * VEC + k] + comb[(size_t)((q + 1) * lpr + lane) * VEC + k];
+                for (int q = 0; q < slots; ++q) at += comb[(size_t)(q * c.lpr + c.lane) * VEC + k];
                 total -= at * at * inv_n;
             }
         }
+        lds_barrier();                                 // the merge slots are free again
+    }
+}
+
+template <int VEC, typename GT, bool CD, int T>
+__device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ G, const TileSlot* tab, char* tiles,
+                            int n, int deg, Pitch ld, int64_t ncg, float neg_lr, int lpr, double inv_n) {
+    typedef typename Cols<VEC>::T V;
+    typedef typename RawG<GT, VEC>::T GR;
+    const Cols<VEC> tag{};
+    constexpr int RB = TileShape<T>::RB, SB = TileShape<T>::SB;
+    TileCtx<VEC> c;
+    c.tab = tab;
+    c.n = n;
+    c.deg = deg;
+    c.lpr = lpr;
+    c.lane = c.tlane = threadIdx.x % lpr;
+    c.rg = threadIdx.x / lpr;
+    c.nrg = T / lpr;
+    c.neg_lr = neg_lr;
+    const int lane = c.lane, rg = c.rg, nrg = c.nrg;
+    const int nb = ((n + nrg - 1) / nrg + RB - 1) / RB;      // batches per tile: the same for every lane
+    const size_t tile_bytes = (((size_t)n * lpr * sizeof(V)) + 15) & ~(size_t)15;
+    V* cur = reinterpret_cast<V*>(tiles);
+    V* nxt = reinterpret_cast<V*>(tiles + tile_bytes);
+    double* comb = reinterpret_cast<double*>(tiles + 2 * tile_bytes);   // [T / 64][lpr][VEC], CD only
+    const int64_t ntiles = (ncg + lpr - 1) / lpr;
+    const int64_t step = gridDim.x;
+    int64_t t = blockIdx.x;
+    if (t >= ntiles) return 0.0;                             // uniform: the whole workgroup has nothing to do
+    double total = 0.0;
+    TileStats<VEC> st;
+
+    // Loads of one batch of one tile: X rows into xs, gradient rows into g (nothing beyond the last tile or the
+    // ragged end of the rows).
+    auto col_of = [&](int64_t tile) { return (tile * lpr + lane) * VEC; };
+    auto live = [&](int64_t tile) { return tile < ntiles && tile * lpr + lane < ncg; };
+    // `q` is the lane's row group: rg, or the same number held in a scalar register where it is known to be
+    // uniform over the wavefront (row offsets and table addresses then cost no vector registers).
+    auto load_x = [&](int q, int64_t tile, int b, V (&xs)[RB]) {
+        const bool on = live(tile);
+        const int64_t col = col_of(tile);
+#pragma unroll
+        for (int u = 0; u < RB; ++u) {
+            const int r = q + (b * RB + u) * nrg;
+            if (on && r < n) xs[u] = ld_x(X + (int64_t)r * ld.x + col, tag);
+        }
+    };
+    auto load_g = [&](int q, int64_t tile, int b, GR (&g)[RB]) {
+        const bool on = live(tile);
+        const int64_t col = col_of(tile);
+#pragma unroll
+        for (int u = 0; u < RB; ++u) {
+            const int r = q + (b * RB + u) * nrg;
+            if (on && r < n) g[u] = ld_g_raw(G + (int64_t)r * ld.g + col, tag);
+        }
+    };
+    auto stash = [&](int q, int64_t tile, int b, V* buf, const V (&xs)[RB]) {
+        const bool on = live(tile);
+#pragma unroll
+        for (int u = 0; u < RB; ++u) {
+            const int r = q + (b * RB + u) * nrg;
+            if (on && r < n) buf[r * lpr + lane] = xs[u];
+        }
+    };
+
+    // First tile: straight into `cur`.
+    for (int b = 0; b < nb; ++b) {
+        V xs[RB];
+        load_x(rg, t, b, xs);
+        stash(rg, t, b, cur, xs);
+    }
+
+    if (T > 256 && nb == 1 && lpr >= 64) {
+        // A tile is one batch of whole-wavefront rows (n <= 64 with 1 KB row segments, fewer learners with wider
+        // ones): X runs TWO tiles ahead in registers and the gradients one, so that a load has a whole tile's time
+        // to arrive before its value is needed and about two tiles of X are in flight per compute unit at any
+        // time.  The two register sets swap roles every tile (the loop is unrolled by two so that no register is
+        // copied: a copy would wait for a load issued a moment ago).  Every load and store in this loop is
+        // unconditional (see tile_rows): rows, columns and tiles beyond the end are clamped to the last valid one.
+        const int q = __builtin_amdgcn_readfirstlane(rg);      // a row group is whole wavefronts: its number is a scalar
+        c.rg = q;
+        const int last_row = n - 1;
+        auto cge_of = [&](int64_t tile) {                       // the lane's column group in `tile`, clamped
+            const int64_t cg = tile * lpr + lane;
+            return cg < ncg ? cg : ncg - 1;
+        };
+        auto ld_xs = [&](int64_t tile, V (&xs)[RB]) {
+            const int64_t col = cge_of(tile) * VEC;
+#pragma unroll
+            for (int u = 0; u < RB; ++u) {
+                int r = q + u * nrg;
+                r = r < last_row ? r : last_row;
+                xs[u] = ld_x(X + (int64_t)r * ld.x + col, tag);
+            }
+        };
+        auto ld_gs = [&](int64_t tile, GR (&g)[RB], GR& gp) {
+            const int64_t col = cge_of(tile) * VEC;
+#pragma unroll
+            for (int u = 0; u < RB; ++u) {
+                int r = q + u * nrg;
+                r = r < last_row ? r : last_row;
+                g[u] = ld_g_raw(G + (int64_t)r * ld.g + col, tag);
+            }
+            if (CD) gp = ld_g_raw(G + col, tag);
+        };
+        V xa[RB], xb[RB];
+        GR ga[RB], gb[RB], g0a = {}, g0b = {};
+        ld_xs(t + step, xa);
+        ld_gs(t, ga, g0a);
+        lds_barrier();
+        // one tile: issue X of tile t + 2 step into `xi` and gradients of t + step into `gi`, compute tile t with
+        // `gu`, stage X of tile t + step (issued one tile ago into `xw`) into the other buffer
+#define PSGD_TILE_ROUND(xw, xi, gu, gi, g0u, g0i)                                                                        \
+    do {                                                                                                                 \
+        ld_xs(t + 2 * step, xi);                                                                                         \
+        ld_gs(t + step, gi, g0i);                                                                                        \
+        const int64_t cge = cge_of(t);                                                                                   \
+        const bool active = t * lpr + lane < ncg;                                                                        \
+        c.tlane = (int)(cge - t * lpr);                                                                                  \
+        if (CD) st.reset();                                                                                              \
+        tile_rows<VEC, CD, RB, SB, true>(c, cur, 0, gu, g0u, true, active, Xout + cge * VEC, ld.o, st);                  \
+        {                                                                                                                \
+            const int lane_n = (int)(cge_of(t + step) - (t + step) * lpr);   /* negative beyond the last tile */          \
+            _Pragma("unroll") for (int u = 0; u < RB; ++u) {                                                             \
+                int r = q + u * nrg;                                                                                     \
+                r = r < last_row ? r : last_row;                                                                         \
+                if (lane_n >= 0) nxt[r * lpr + lane_n] = xw[u];                                                          \
+            }                                                                                                            \
+        }                                                                                                                \
+        tile_finish<VEC, CD, T>(c, comb, active, st, inv_n, total);                                                      \
+        V* sw_ = cur;                                                                                                    \
+        cur = nxt;                                                                                                       \
+        nxt = sw_;                                                                                                       \
+        t += step;                                                                                                       \
+    } while (0)
+        for (;;) {
+            PSGD_TILE_ROUND(xa, xb, ga, gb, g0a, g0b);
+            if (t >= ntiles) break;
+            PSGD_TILE_ROUND(xb, xa, gb, ga, g0b, g0a);
+            if (t >= ntiles) break;
+        }
+#undef PSGD_TILE_ROUND
+        return total;
+    }
+
+    // Several batches per tile: batch b of the next tile travels while batch b of this one is computed, the
+    // gradients one batch ahead.
+    GR gcur[RB], g0 = {};
+    load_g(rg, t, 0, gcur);
+    if (CD && live(t)) g0 = ld_g_raw(G + col_of(t), tag);
+    lds_barrier();
+    for (;;) {
+        const int64_t tn = t + step;
+        const bool active = live(t);
+        GR g0n = {};
+        if (CD) st.reset();
+        for (int b = 0; b < nb; ++b) {
+            V xs[RB];
+            GR gn[RB];
+            load_x(rg, tn, b, xs);
+            if (b + 1 < nb) {
+                load_g(rg, t, b + 1, gn);
+            } else {
+                load_g(rg, tn, 0, gn);
+                if (CD && live(tn)) g0n = ld_g_raw(G + col_of(tn), tag);
+            }
+            tile_rows<VEC, CD, RB, SB, false>(c, cur, b, gcur, g0, b == 0, active, Xout + col_of(t), ld.o, st);
+            stash(rg, tn, b, nxt, xs);
+#pragma unroll
+            for (int u = 0; u < RB; ++u) gcur[u] = gn[u];
+        }
+        g0 = g0n;
+        tile_finish<VEC, CD, T>(c, comb, active, st, inv_n, total);
+        if (tn >= ntiles) break;
+        V* sw = cur;
+        cur = nxt;
+        nxt = sw;
+        t = tn;
     }
     return total;
 }
@@ -535,8 +789,11 @@ inline Sweeps make_sweeps(int64_t ncg, int grid, int threads) {
 
 // T = workgroup size: kRingThreads on long rows, kThreads (four workgroups per CU) where the row is too
 // short to give every CU a large workgroup's worth of column groups twice over.
-template <int VEC, typename GT, bool CD, int T>
-__global__ __launch_bounds__(T) void mix_step_kernel(const float* X, float* Xout, const GT* __restrict__ G,
+// TILES: the kernel also carries the tiled path for tables that are not one ring (short rows: one launch does
+// whatever the table needs).  Without it (long rows) such a table is left to the tiled kernel, which the launcher
+// enqueues right behind this one and which classifies the table the same way; this kernel then writes nothing.
+template <int VEC, typename GT, bool CD, int T, bool TILES>
+__global__ __launch_bounds__(T, 3) void mix_step_kernel(const float* X, float* Xout, const GT* __restrict__ G,
                                                      const int32_t* __restrict__ nbr, const float* __restrict__ w,
                                                      int n, int64_t d, Pitch ld, float neg_lr, int lpr,
                                                      Sweeps sweeps, double* __restrict__ partials) {
@@ -564,8 +821,14 @@ __global__ __launch_bounds__(T) void mix_step_kernel(const float* X, float* Xout
             ring_walk<VEC, GT, CD>(X + col, Xout + col, G + col, l.ring, n, ld, neg_lr, stats, act);
             if (CD && act) total += stats.result(inv_n);
         }
-    } else {
-        total = tile_path<VEC, GT, CD, int, false, T>(X, Xout, G, l, l.nbr, n, ld, ncg, neg_lr, lpr, inv_n);
+    } else if (TILES) {
+        // The slot table in the tiled path's form, then the tile buffers (the ranking arrays that shared this
+        // space are dead: stage_table ended with a barrier on every path that comes here).
+        TileSlot* tab = reinterpret_cast<TileSlot*>(l.scratch);
+        for (int e = threadIdx.x; e < 3 * n; e += T) tab[e] = TileSlot{(uint32_t)(l.nbr[e] * lpr), l.w[e]};
+        __syncthreads();
+        const size_t tab_bytes = (((size_t)n * 3 * sizeof(TileSlot)) + 15) & ~(size_t)15;
+        total = tile_path<VEC, GT, CD, T>(X, Xout, G, tab, l.scratch + tab_bytes, n, 3, ld, ncg, neg_lr, lpr, inv_n);
     }
     if (CD) {
         const double bs = block_sum<T>(total, lds_waves);
@@ -573,22 +836,35 @@ __global__ __launch_bounds__(T) void mix_step_kernel(const float* X, float* Xout
     }
 }
 
-// Any table with `deg` slots per row (sparse doubly stochastic matrices beyond the ring:
-// more neighbours, lazy walks, products of several mixing rounds).  Always the tiled path.
-template <int VEC, typename GT, bool CD>
-__global__ __launch_bounds__(kThreads, 4) void mix_deg_kernel(const float* X, float* Xout, const GT* __restrict__ G,
-                                                           const int32_t* __restrict__ nbr,
-                                                           const float* __restrict__ w, int deg, int n, int64_t d,
-                                                           Pitch ld, float neg_lr, int lpr,
-                                                           double* __restrict__ partials) {
+// Any table with `deg` slots per row (sparse doubly stochastic matrices beyond the ring: more neighbours, lazy
+// walks, products of several mixing rounds, and 3-slot tables that are not one ring).  Always the tiled path.
+// LDS: TileSlot tab[deg n] | two tile buffers | merge slots (plan::tile_plan).
+//
+// skip_rings (3-slot tables only): the launcher enqueues this kernel behind the ring-walk kernel because only
+// the device can tell which of the two a table needs; both classify it with the same code, and the one it does
+// not belong to writes nothing (and contributes 0 to the distance).
+template <int VEC, typename GT, bool CD, int T>
+__global__ __launch_bounds__(T) void mix_deg_kernel(const float* X, float* Xout, const GT* __restrict__ G,
+                                                    const int32_t* __restrict__ nbr, const float* __restrict__ w,
+                                                    int deg, int n, int64_t d, Pitch ld, float neg_lr, int lpr,
+                                                    int skip_rings, double* __restrict__ partials) {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-    __shared__ double lds4[4];
-    const Lds l = carve(lds_raw, n, deg);
+    __shared__ double lds_waves[T / 64];
+    const size_t tab_bytes = (((size_t)n * deg * sizeof(TileSlot)) + 15) & ~(size_t)15;
+    if (skip_rings) {
+        // the tile area is free until the first tile is loaded: classify there
+        const int kind = stage_table<T>(nbr, w, n, carve(lds_raw + tab_bytes, n));
+        if (kind != kTableGeneral) {
+            // one ring: the other kernel's work.  Invalid: it has raised the flag; the distance is NaN.
+            if (CD && threadIdx.x == 0) partials[blockIdx.x] = kind == kTableRing ? 0.0 : __builtin_nan("");
+            return;
+        }
+    }
+    TileSlot* tab = reinterpret_cast<TileSlot*>(lds_raw);
     int ok = 1;
-    for (int e = threadIdx.x; e < deg * n; e += kThreads) {
+    for (int e = threadIdx.x; e < deg * n; e += T) {
         const int v = nbr[e];
-        l.nbr16[e] = (uint16_t)(v * lpr);   // tile offset of the row (n * lpr <= 8192 by the tile budget)
-        l.w[e] = w[e];
+        tab[e] = TileSlot{(uint32_t)(v * lpr), w[e]};
         ok &= (unsigned)v < (unsigned)n;
     }
     if (!__syncthreads_and(ok)) {
@@ -596,15 +872,10 @@ __global__ __launch_bounds__(kThreads, 4) void mix_deg_kernel(const float* X, fl
         if (CD && threadIdx.x == 0) partials[blockIdx.x] = __builtin_nan("");
         return;
     }
-    const int nrg = kThreads / lpr;
-    const double inv_n = 1.0 / (double)n;
-    double total;
-    if (n % (kTileUnroll * nrg) == 0)
-        total = tile_path<VEC, GT, CD, uint16_t, true>(X, Xout, G, l, l.nbr16, n, ld, d / VEC, neg_lr, lpr, inv_n, deg);
-    else
-        total = tile_path<VEC, GT, CD, uint16_t, false>(X, Xout, G, l, l.nbr16, n, ld, d / VEC, neg_lr, lpr, inv_n, deg);
+    const double total = tile_path<VEC, GT, CD, T>(X, Xout, G, tab, lds_raw + tab_bytes, n, deg, ld, d / VEC, neg_lr, lpr,
+                                                   1.0 / (double)n);
     if (CD) {
-        const double bs = block_sum(total, lds4);
+        const double bs = block_sum<T>(total, lds_waves);
         if (threadIdx.x == 0) partials[blockIdx.x] = bs;
     }
 }
@@ -652,7 +923,7 @@ __global__ __launch_bounds__(T) void mix_full_kernel(const float* X, float* Xout
         for (int k = 0; k < VEC; ++k) sum[k] = 0.0;
         int r = 0;
         for (; r + kUnroll <= n; r += kUnroll) {
-            __syncthreads();
+            lockstep_barrier();
             V xs[kUnroll];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) xs[u] = ld_x(xc + (int64_t)(r + u) * ld.x, tag);
@@ -665,7 +936,7 @@ __global__ __launch_bounds__(T) void mix_full_kernel(const float* X, float* Xout
         if (CD) stats.reset();
         r = 0;
         for (; r + kUnroll <= n; r += kUnroll) {
-            __syncthreads();
+            lockstep_barrier();
             V gs[kUnroll];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) gs[u] = ld_g(gc + (int64_t)(r + u) * ld.g, tag);
@@ -777,6 +1048,60 @@ __global__ __launch_bounds__(kThreads) void synth_grad_rows_kernel(const float* 
             st_x(g + (int64_t)r * ldg + col,
                  vfma(c, ld_x(xp + (int64_t)r * ldx + col, tag), ld_x(noise + (int64_t)r * ldn + col, tag)));
     }
+}
+
+// ---------------------------------------------------------------------------------------
+// Reference streams (measurement support, not a step of the method): the memory traffic of the step with the
+// mixing taken out, in the very form the step kernels give it -- a lane owns one 128-bit column group and
+// walks the n rows, the workgroup's wavefronts sweep the rows in lockstep batches, the column groups are split
+// evenly over a persistent grid.  KIND 0 only reads X and G, KIND 1 only writes X_out, KIND 2 is
+// X_out = X + a * G (the step's 4 + 2 + 4 or 4 + 4 + 4 bytes per element, no neighbours).  The rate these
+// reach is what the chip's memory system gives this access pattern; the step is measured against it.
+// ---------------------------------------------------------------------------------------
+enum { kRefRead = 0, kRefWrite = 1, kRefAxpy = 2 };
+
+template <int KIND, typename GT, int T>
+__global__ __launch_bounds__(T) void reference_stream_kernel(const float* X, float* Xout, const GT* __restrict__ G,
+                                                             int n, int64_t d, Pitch ld, float a, Sweeps sweeps) {
+    const Cols<4> tag{};
+    const int64_t ncg = d / 4;
+    f32x4 keep = splat4(0.0f);
+    for (int64_t sw = 0; sw < sweeps.count; ++sw) {
+        const int64_t base = sweeps.base(sw), cg = base + threadIdx.x;
+        if (base >= ncg) break;                                  // nothing left for this workgroup (uniform)
+        const int64_t end = base + sweeps.chunk < ncg ? base + sweeps.chunk : ncg;   // uniform
+        const bool act = cg < end;                               // an idle lane shadows column group 0
+        const int64_t col = (act ? cg : 0) * 4;
+        const float* xc = X + col;
+        const GT* gc = G + col;
+        float* oc = Xout + col;
+        int r = 0;
+        for (; r + kUnroll <= n; r += kUnroll) {
+            lockstep_barrier();
+            f32x4 xs[kUnroll], gs[kUnroll];
+            if (KIND != kRefWrite) {
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    xs[u] = ld_x(xc + (int64_t)(r + u) * ld.x, tag);
+                    gs[u] = ld_g(gc + (int64_t)(r + u) * ld.g, tag);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                if (KIND == kRefRead) keep += xs[u] + gs[u];
+                if (KIND == kRefWrite && act) st_x(oc + (int64_t)(r + u) * ld.o, splat4(a));
+                if (KIND == kRefAxpy && act) st_x(oc + (int64_t)(r + u) * ld.o, vfma(a, gs[u], xs[u]));
+            }
+        }
+        for (; r < n; ++r) {
+            if (KIND == kRefRead) keep += ld_x(xc + (int64_t)r * ld.x, tag) + ld_g(gc + (int64_t)r * ld.g, tag);
+            if (KIND == kRefWrite && act) st_x(oc + (int64_t)r * ld.o, splat4(a));
+            if (KIND == kRefAxpy && act)
+                st_x(oc + (int64_t)r * ld.o, vfma(a, ld_g(gc + (int64_t)r * ld.g, tag), ld_x(xc + (int64_t)r * ld.x, tag)));
+        }
+    }
+    // The loads of the read-only stream must have an observer: a store that the data never triggers.
+    if (KIND == kRefRead && __float_as_uint(keep.x + keep.y + keep.z + keep.w) == 0x7FC0BEEFu) Xout[0] = keep.x;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1004,20 +1329,32 @@ bool scalar_overlaps(const double* p, const void* B, int64_t ldb, size_t rb, int
     return false;
 }
 
+// A workgroup gets 64 KB of dynamic LDS by default; a kernel that is to be launched with more is opted in.
+int allow_lds(const void* fn, size_t lds_bytes) {
+    if (lds_bytes <= 64 * 1024 - 256) return PSGD_OK;
+    // the most this library ever asks for (the kernels' few hundred bytes of static LDS come on top of it)
+    const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsCapLarge);
+    if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(MaxDynamicSharedMemorySize)");
+    return PSGD_OK;
+}
+constexpr int kLaunchRefused = INT32_MIN;
+
 // Launches one instantiation of the mix kernel on a persistent grid sized to what is
 // actually resident: min(kGridPerCu, occupancy for this LDS size) workgroups per CU.
-// Returns the grid size, or minus the grid size (and launches nothing) when the fused distance would
-// need more than `slots` partials.
-template <int VEC, typename GT, bool CD, int T>
+// Returns the grid size, minus the grid size (and launches nothing) when the fused distance would need more
+// than `slots` partials, or kLaunchRefused when the runtime refuses the LDS size.
+template <int VEC, typename GT, bool CD, int T, bool TILES>
 int launch_mix_t(const DeviceInfo& di, size_t lds_bytes, hipStream_t s, const float* X, float* X_out, const GT* G,
                  const int32_t* nbr, const float* w, int n, int64_t d, Pitch ld, float neg_lr, int lpr,
                  double* partials, int slots) {
-    const int occ = resident_per_cu(reinterpret_cast<const void*>(mix_step_kernel<VEC, GT, CD, T>), lds_bytes, T);
+    const void* fn = reinterpret_cast<const void*>(mix_step_kernel<VEC, GT, CD, T, TILES>);
+    if (allow_lds(fn, lds_bytes)) return kLaunchRefused;
+    const int occ = resident_per_cu(fn, lds_bytes, T);
     const int want = T == kThreads ? kGridPerCu : 1;
     const int grid = persistent_grid(di, d / VEC, occ < want ? occ : want, T);
     if (CD && grid > slots) return -grid;   // one partial per workgroup must fit the caller's buffer: nothing is launched
-    hipLaunchKernelGGL((mix_step_kernel<VEC, GT, CD, T>), dim3(grid), dim3(T), lds_bytes, s, X, X_out, G, nbr, w, n, d,
-                       ld, neg_lr, lpr, make_sweeps(d / VEC, grid, T), partials);
+    hipLaunchKernelGGL((mix_step_kernel<VEC, GT, CD, T, TILES>), dim3(grid), dim3(T), lds_bytes, s, X, X_out, G, nbr, w,
+                       n, d, ld, neg_lr, lpr, make_sweeps(d / VEC, grid, T), partials);
     return grid;
 }
 
@@ -1031,10 +1368,11 @@ template <int VEC, typename GT, bool CD>
 int launch_mix(const DeviceInfo& di, bool big, size_t lds_bytes, hipStream_t s, const float* X, float* X_out,
                const GT* G, const int32_t* nbr, const float* w, int n, int64_t d, Pitch ld, float neg_lr, int lpr,
                double* partials, int slots) {
-    return big ? launch_mix_t<VEC, GT, CD, kRingThreads>(di, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials, slots)
-               : launch_mix_t<VEC, GT, CD, kThreads>(di, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials, slots);
+    return big ? launch_mix_t<VEC, GT, CD, kRingThreads, false>(di, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr,
+                                                                partials, slots)
+               : launch_mix_t<VEC, GT, CD, kThreads, true>(di, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr,
+                                                           partials, slots);
 }
-
 
 // Pitches are in elements of the array they belong to.
 template <typename GT>
@@ -1096,64 +1434,87 @@ int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
     const bool vec4 = (d % 4 == 0) && (ldx % 4 == 0) && (ldo % 4 == 0) && (ldg % 4 == 0) && aligned_to(X, 16) &&
                       aligned_to(X_out, 16) && aligned_to(G, 4 * sizeof(GT));
     const int vec = vec4 ? 4 : 1;
-    // Tile shape of the tiled path: widest power-of-two lane count whose tile (plus the
-    // combine arrays of the fused distance) fits the budget and the 64 KB a workgroup may use.
-    const size_t lds_limit = deg == 3 ? 64 * 1024 - 64 : kDegLdsLimit;   // wide tables may need more than 64 KB
-    const bool big = deg == 3 && long_rows(*di, d / vec);
-    const int wg_threads = big ? kRingThreads : kThreads;
-    const size_t table_bytes = (lds_table_bytes(n, deg) + 15) & ~(size_t)15;
-    const size_t tile_budget = (size_t)kTileBytes;
-    int lpr = 64;
-    size_t scratch_bytes = 0;
-    for (;; lpr >>= 1) {
-        const size_t tile = (size_t)n * lpr * vec * sizeof(float);
-        scratch_bytes = tile + (want_cd ? tile_cd_bytes(lpr, vec, wg_threads) : 0);
-        if ((tile <= tile_budget && table_bytes + scratch_bytes <= lds_limit) || lpr == 1) break;
-    }
-    if (scratch_bytes < (size_t)n * 4 * sizeof(int)) scratch_bytes = (size_t)n * 4 * sizeof(int);
-    const size_t lds_bytes = table_bytes + scratch_bytes;
-    if (lds_bytes > lds_limit)
-        return fail(PSGD_EINVAL, "%s: n=%d, deg=%d needs %zu bytes of LDS", name, n, deg, lds_bytes);
-
+    // Long rows take a large workgroup that is alone on its compute unit; short ones four small workgroups.
+    const bool big = long_rows(*di, d / vec);
     const float neg_lr = -lr;
     const Pitch ld{ldx, ldo, ldg};
-    int grid = 0;
-    if (deg != 3) {
-        const int64_t ntiles = (d / vec + lpr - 1) / lpr;
-        const void* fn = vec4 ? (want_cd ? (const void*)mix_deg_kernel<4, GT, true> : (const void*)mix_deg_kernel<4, GT, false>)
-                              : (want_cd ? (const void*)mix_deg_kernel<1, GT, true> : (const void*)mix_deg_kernel<1, GT, false>);
-        if (lds_bytes > 64 * 1024 - 64) {
-            // opt in to more than the default 64 KB of dynamic LDS
-            const hipError_t ea = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDegLdsLimit);
-            if (ea != hipSuccess) return hip_fail(ea, "hipFuncSetAttribute(MaxDynamicSharedMemorySize)");
+    int grid = 0;        // partial sums written so far (the fused distance sums this many)
+    const size_t classify = lds_table_bytes(n) + (size_t)n * 4 * sizeof(int);   // the 3-slot kernels' table copy + ranking arrays
+    if (deg == 3) {
+        // The ring-walk kernel does the work when the table is one ring (every table of Sec. 3).  On short rows
+        // it also carries the tiled path, so that one launch serves any table; on long rows the tiled kernel
+        // follows it (below), because there each path wants its own workgroup shape and registers.
+        size_t ring_lds = classify;
+        int ring_lpr = 0;
+        if (!big) {
+            plan::TilePlan rp = plan::tile_plan(n, 3, vec, kThreads, want_cd, kLdsCapSmall, lds_table_bytes(n), TileShape<kThreads>::RB);
+            if (rp.lpr == 0) rp = plan::tile_plan(n, 3, vec, kThreads, want_cd, kLdsCapLarge, lds_table_bytes(n), TileShape<kThreads>::RB);
+            if (rp.lpr == 0) return fail(PSGD_EINVAL, "%s: n=%d does not fit the tiled path's LDS", name, n);
+            ring_lpr = rp.lpr;
+            if (rp.total > ring_lds) ring_lds = rp.total;
         }
-        int per_cu = resident_per_cu(fn, lds_bytes);
-        if (per_cu > 2 * kGridPerCu) per_cu = 2 * kGridPerCu;
-        grid = deg_grid(ntiles, di->cus, per_cu);
-        const dim3 g(grid), b(kThreads);
         if (vec4 && want_cd)
-            hipLaunchKernelGGL((mix_deg_kernel<4, GT, true>), g, b, lds_bytes, s, X, X_out, G, nbr, w, deg, n, d, ld,
-                               neg_lr, lpr, partials);
+            grid = launch_mix<4, GT, true>(*di, big, ring_lds, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, ring_lpr, partials, slots);
         else if (vec4)
-            hipLaunchKernelGGL((mix_deg_kernel<4, GT, false>), g, b, lds_bytes, s, X, X_out, G, nbr, w, deg, n, d, ld,
-                               neg_lr, lpr, partials);
+            grid = launch_mix<4, GT, false>(*di, big, ring_lds, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, ring_lpr, partials, slots);
         else if (want_cd)
-            hipLaunchKernelGGL((mix_deg_kernel<1, GT, true>), g, b, lds_bytes, s, X, X_out, G, nbr, w, deg, n, d, ld,
-                               neg_lr, lpr, partials);
+            grid = launch_mix<1, GT, true>(*di, big, ring_lds, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, ring_lpr, partials, slots);
         else
-            hipLaunchKernelGGL((mix_deg_kernel<1, GT, false>), g, b, lds_bytes, s, X, X_out, G, nbr, w, deg, n, d, ld,
-                               neg_lr, lpr, partials);
-    } else if (vec4 && want_cd)
-        grid = launch_mix<4, GT, true>(*di, big, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials, slots);
-    else if (vec4)
-        grid = launch_mix<4, GT, false>(*di, big, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials, slots);
-    else if (want_cd)
-        grid = launch_mix<1, GT, true>(*di, big, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials, slots);
-    else
-        grid = launch_mix<1, GT, false>(*di, big, lds_bytes, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, lpr, partials, slots);
+            grid = launch_mix<1, GT, false>(*di, big, ring_lds, s, X, X_out, G, nbr, w, n, d, ld, neg_lr, ring_lpr, partials, slots);
+        if (grid == kLaunchRefused) return PSGD_EHIP;   // allow_lds has recorded the reason
+        if (grid < 0)
+            return fail(PSGD_EINVAL, "%s: this launch needs %d partial sums, the buffer holds %d", name, -grid, slots);
+        const hipError_t e1 = hipGetLastError();
+        if (e1 != hipSuccess) return hip_fail(e1, name);
+    }
+    if (deg != 3 || big) {
+        // Tiled kernel: every table with another slot count, and behind the ring walk for 3-slot tables, where
+        // it does the work only if the table turns out not to be one ring (decided on the device by both).
+        const int wg_threads = big ? kTileThreads : kThreads;
+        const size_t base = 0;
+        const int rpb = big ? TileShape<kTileThreads>::RB : TileShape<kThreads>::RB;
+        plan::TilePlan tp = plan::tile_plan(n, deg, vec, wg_threads, want_cd, big ? kLdsCapLarge : kLdsCapSmall, base, rpb);
+        if (tp.lpr == 0 && !big) tp = plan::tile_plan(n, deg, vec, wg_threads, want_cd, kLdsCapLarge, base, rpb);
+        if (tp.lpr == 0)
+            return fail(PSGD_EINVAL, "%s: n=%d, deg=%d does not fit the tiled path's LDS", name, n, deg);
+        const int lpr = tp.lpr;
+        size_t lds_bytes = tp.total;
+        if (deg == 3 && lds_bytes < tp.tab_bytes + classify) lds_bytes = tp.tab_bytes + classify;
+        const int64_t ntiles = (d / vec + lpr - 1) / lpr;
+        const int first = grid;
+        int tgrid = 0;
+#define PSGD_DEG_LAUNCH(VEC, CD, T)                                                                                     \
+    do {                                                                                                                \
+        const void* fn = reinterpret_cast<const void*>(mix_deg_kernel<VEC, GT, CD, T>);                                 \
+        if (int rc = allow_lds(fn, lds_bytes)) return rc;                                                               \
+        int per_cu = resident_per_cu(fn, lds_bytes, T);                                                                 \
+        if (per_cu > 2 * kGridPerCu) per_cu = 2 * kGridPerCu;                                                           \
+        tgrid = deg_grid(ntiles, di->cus, per_cu);                                                                      \
+        if (CD && first + tgrid > slots) {   /* one partial per workgroup: a smaller persistent grid still covers */    \
+            tgrid = slots - first;           /* every tile                                                        */    \
+            if (tgrid < 1) {                                                                                            \
+                tgrid = -(first + 1);                                                                                   \
+                break;                                                                                                  \
+            }                                                                                                           \
+        }                                                                                                               \
+        hipLaunchKernelGGL((mix_deg_kernel<VEC, GT, CD, T>), dim3(tgrid), dim3(T), lds_bytes, s, X, X_out, G, nbr, w,   \
+                           deg, n, d, ld, neg_lr, lpr, deg == 3 ? 1 : 0, CD ? partials + first : partials);             \
+    } while (0)
+#define PSGD_DEG_PICK(VEC, CD)                                                                                          \
+    do {                                                                                                                \
+        if (big) PSGD_DEG_LAUNCH(VEC, CD, kTileThreads);                                                                \
+        else PSGD_DEG_LAUNCH(VEC, CD, kThreads);                                                                        \
+    } while (0)
+        if (vec4 && want_cd) PSGD_DEG_PICK(4, true);
+        else if (vec4) PSGD_DEG_PICK(4, false);
+        else if (want_cd) PSGD_DEG_PICK(1, true);
+        else PSGD_DEG_PICK(1, false);
+#undef PSGD_DEG_PICK
+#undef PSGD_DEG_LAUNCH
+        grid = tgrid < 0 ? tgrid : first + tgrid;
+    }
     if (grid < 0)
-        return fail(PSGD_EINVAL, "%s: this launch needs %d partial sums, the static scratch holds %d (PSGD_STATIC_SLOTS)",
-                    name, -grid, (int)PSGD_STATIC_SLOTS);
+        return fail(PSGD_EINVAL, "%s: this launch needs %d partial sums, the buffer holds %d", name, -grid, slots);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, name);
     if (want_cd) {
@@ -1474,6 +1835,56 @@ int psgd_synth_grad_ex(const float* X_prev, int64_t ldx, const float* noise, int
                            n, d, c);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "synth_grad_rows_kernel");
+    return PSGD_OK;
+}
+
+int psgd_reference_stream(int kind, const float* X, int64_t ldx, float* X_out, int64_t ldo, const void* G, int64_t ldg,
+                          int g_is_bf16, int n, int64_t d, float a, void* stream) {
+    using namespace psgd;
+    clear_error();
+    if (kind != kRefRead && kind != kRefWrite && kind != kRefAxpy)
+        return fail(PSGD_EINVAL, "psgd_reference_stream: kind=%d", kind);
+    if (g_is_bf16 != 0 && g_is_bf16 != 1) return fail(PSGD_EINVAL, "psgd_reference_stream: g_is_bf16=%d", g_is_bf16);
+    if (!X || !X_out || !G) return fail(PSGD_EINVAL, "psgd_reference_stream: null pointer");
+    if (n < 1 || n > PSGD_MAX_N || d < 0) return fail(PSGD_EINVAL, "psgd_reference_stream: n=%d d=%lld", n, (long long)d);
+    if (n > 1 && (ldx < d || ldo < d || ldg < d))
+        return fail(PSGD_EINVAL, "psgd_reference_stream: a row pitch is smaller than d");
+    if (n == 1) ldx = ldo = ldg = d;
+    const size_t gsz = g_is_bf16 ? 2 : 4;
+    if (d % 4 || ldx % 4 || ldo % 4 || ldg % 4 || !aligned_to(X, 16) || !aligned_to(X_out, 16) || !aligned_to(G, 4 * gsz))
+        return fail(PSGD_EALIGN, "psgd_reference_stream: needs d and the pitches in multiples of 4 and 128-bit aligned rows");
+    const int64_t ldmax = ldx > ldo ? (ldx > ldg ? ldx : ldg) : (ldo > ldg ? ldo : ldg);
+    if (ldmax > 0 && (int64_t)n > INT64_MAX / 8 / ldmax) return fail(PSGD_EINVAL, "psgd_reference_stream: n * pitch overflows");
+    const size_t xrow = (size_t)d * 4, grow = (size_t)d * gsz;
+    if (kind != kRefRead && (rows_overlap(X, ldx * 4, xrow, X_out, ldo * 4, xrow, n) ||
+                             rows_overlap(G, ldg * (int64_t)gsz, grow, X_out, ldo * 4, xrow, n)))
+        return fail(PSGD_EALIAS, "psgd_reference_stream: X_out overlaps an input");
+    if (d == 0) return PSGD_OK;
+    DeviceInfo* di = nullptr;
+    if (int rc = device_info(&di)) return rc;
+    const bool big = long_rows(*di, d / 4);
+    const int threads = big ? kRingThreads : kThreads;
+    const int grid = persistent_grid(*di, d / 4, big ? 1 : kGridPerCu, threads);
+    const Sweeps sw = make_sweeps(d / 4, grid, threads);
+    const Pitch ld{ldx, ldo, ldg};
+    hipStream_t s = static_cast<hipStream_t>(stream);
+#define PSGD_REF_LAUNCH(KIND, GT, T)                                                                                    \
+    hipLaunchKernelGGL((reference_stream_kernel<KIND, GT, T>), dim3(grid), dim3(T), 0, s, X, X_out,                      \
+                       static_cast<const GT*>(G), n, d, ld, a, sw)
+#define PSGD_REF_KIND(KIND)                                                                                             \
+    do {                                                                                                                \
+        if (g_is_bf16 && big) PSGD_REF_LAUNCH(KIND, uint16_t, kRingThreads);                                            \
+        else if (g_is_bf16) PSGD_REF_LAUNCH(KIND, uint16_t, kThreads);                                                  \
+        else if (big) PSGD_REF_LAUNCH(KIND, float, kRingThreads);                                                       \
+        else PSGD_REF_LAUNCH(KIND, float, kThreads);                                                                    \
+    } while (0)
+    if (kind == kRefRead) PSGD_REF_KIND(kRefRead);
+    else if (kind == kRefWrite) PSGD_REF_KIND(kRefWrite);
+    else PSGD_REF_KIND(kRefAxpy);
+#undef PSGD_REF_KIND
+#undef PSGD_REF_LAUNCH
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "reference_stream_kernel");
     return PSGD_OK;
 }
 

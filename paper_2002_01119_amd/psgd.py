@@ -15,7 +15,7 @@ TOPO_RAND_RING = 1
 TOPO_FULL = 2
 DEG = 3
 MAX_N = 512
-STATIC_SLOTS = 1024
+STATIC_SLOTS = 2048
 
 OK, EINVAL, EALIAS, EALIGN, EHIP = 0, -1, -2, -3, -4
 
@@ -25,7 +25,7 @@ _lib = None
 EXPORTS = (
     "psgd_build_mixing", "psgd_build_mixing_device", "psgd_mix_step", "psgd_mix_step_bf16g", "psgd_mix_step_cd",
     "psgd_mix_step_cd_bf16g", "psgd_mix_step_ex", "psgd_mix_step_cd_static", "psgd_mix_step_deg", "psgd_mix_full", "psgd_consensus_dist", "psgd_consensus_dist_ex",
-    "psgd_consensus_dist_async", "psgd_synth_grad", "psgd_synth_grad_ex", "psgd_device_status", "psgd_last_error",
+    "psgd_consensus_dist_async", "psgd_synth_grad", "psgd_synth_grad_ex", "psgd_reference_stream", "psgd_device_status", "psgd_last_error",
     "psgd_version",
 )
 
@@ -87,6 +87,9 @@ def load(reload=False):
     lib.psgd_synth_grad_ex.restype = ctypes.c_int
     lib.psgd_synth_grad_ex.argtypes = [vp, ctypes.c_int64, vp, ctypes.c_int64, vp, ctypes.c_int64, ctypes.c_int,
                                        ctypes.c_int64, ctypes.c_float, vp]
+    lib.psgd_reference_stream.restype = ctypes.c_int
+    lib.psgd_reference_stream.argtypes = [ctypes.c_int, vp, ctypes.c_int64, vp, ctypes.c_int64, vp, ctypes.c_int64,
+                                          ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_float, vp]
     lib.psgd_device_status.restype = ctypes.c_int
     lib.psgd_device_status.argtypes = [ctypes.c_int]
     lib.psgd_last_error.restype = ctypes.c_char_p
@@ -322,6 +325,31 @@ def synth_grad(X_prev, noise, G, c, stream=None):
     _, _, ldg = _rows_cols_pitch(G)
     _check(load().psgd_synth_grad_ex(X_prev.data_ptr(), ldx, noise.data_ptr(), ldn, G.data_ptr(), ldg, n, d,
                                      float(c), _stream_handle(stream)))
+
+
+REF_READ, REF_WRITE, REF_AXPY = 0, 1, 2
+
+
+def reference_stream(kind, X, X_out, G, a=0.0, stream=None):
+    """Enqueue a reference stream over [n, d] tensors laid out as for mix_step (measurement support):
+    REF_READ reads X and G, REF_WRITE fills X_out with `a`, REF_AXPY writes X_out = X + a * G."""
+    import torch
+    n, d, ldx = _rows_cols_pitch(X)
+    no, do, ldo = _rows_cols_pitch(X_out)
+    ng, dg, ldg = _rows_cols_pitch(G)
+    if (no, do) != (n, d) or (ng, dg) != (n, d):
+        raise ValueError("X, X_out and G must have one shape")
+    if X.dtype != torch.float32 or X_out.dtype != torch.float32:
+        raise ValueError("X and X_out must be float32")
+    if G.dtype == torch.float32:
+        bf16 = 0
+    elif G.dtype in (torch.bfloat16, torch.int16, torch.uint16):
+        bf16 = 1
+    else:
+        raise ValueError("G must be float32 or bfloat16 bit patterns")
+    _on_current_device(X, X_out, G)
+    _check(load().psgd_reference_stream(int(kind), X.data_ptr(), ldx, X_out.data_ptr(), ldo, G.data_ptr(), ldg, bf16,
+                                        n, d, float(a), _stream_handle(stream)))
 
 
 def device_status(clear=True):

@@ -81,6 +81,40 @@ int main() {
     CHECK(persistent_grid(256, 25000000, 1, 768) == 256, "workload 5 grid");
     CHECK(persistent_grid(256, 1000, 4, 256) == 4, "short rows take one workgroup per 256 items");
     CHECK(deg_grid(1 << 30, 1024, 8) == kMaxGrid, "deg_grid clamp");
+    // LDS plan of the tiled path: the widest power-of-two lane count whose slot table, two tile buffers and merge
+    // slots fit the cap; workload shapes get full 1 KB row segments (wider for few learners), and nothing ever
+    // exceeds the cap
+    const size_t large = 160 * 1024 - 1024, small_cap = 40 * 1024 - 256;
+    for (int n : {1, 2, 8, 16, 64, 65, 128, 300, 512})
+        for (int deg : {1, 3, 5, 8, 13, 32}) {
+            if ((long)n * deg > 4096) continue;
+            for (int vec : {1, 4})
+                for (int threads : {256, 512})
+                    for (bool cd : {false, true})
+                        for (size_t cap : {small_cap, large}) {
+                            const int rpb = threads > 256 ? 8 : 4;
+                            const TilePlan p = tile_plan(n, deg, vec, threads, cd, cap, 0, rpb);
+                            if (p.lpr == 0) {
+                                CHECK(cap == small_cap, "n=%d deg=%d vec=%d does not fit the large cap", n, deg, vec);
+                                continue;
+                            }
+                            CHECK(p.lpr >= 1 && p.lpr <= threads && (p.lpr & (p.lpr - 1)) == 0, "lpr %d", p.lpr);
+                            const int nrg = threads / p.lpr;
+                            CHECK(p.lpr <= 64 || (n + nrg - 1) / nrg <= rpb, "n=%d: %d lanes per row leave %d rows per lane", n,
+                                  p.lpr, (n + nrg - 1) / nrg);
+                            CHECK(p.total <= cap, "n=%d deg=%d: %zu bytes over the cap %zu", n, deg, p.total, cap);
+                            CHECK(p.tab_bytes >= (size_t)n * deg * 8 && p.tab_bytes % 16 == 0, "slot table size");
+                            CHECK(p.tile_bytes >= (size_t)n * p.lpr * vec * 4 && p.tile_bytes % 16 == 0, "tile size");
+                            const size_t slots = p.lpr <= 64 ? threads / 64 : nrg;
+                            CHECK(p.comb_bytes == (cd ? slots * p.lpr * vec * 8 : 0), "merge slots");
+                            CHECK(p.total == p.tab_bytes + 2 * p.tile_bytes + p.comb_bytes, "total");
+                        }
+        }
+    CHECK(tile_plan(64, 3, 4, 512, true, large, 0, 8).lpr == 64, "n = 64: 1 KB row segments with the distance");
+    CHECK(tile_plan(64, 13, 4, 512, true, large, 0, 8).lpr == 64, "n = 64, 13 slots");
+    CHECK(tile_plan(128, 3, 4, 512, true, large, 0, 8).lpr == 32, "n = 128: 512-byte row segments");
+    CHECK(tile_plan(16, 3, 4, 512, true, large, 0, 8).lpr == 256, "n = 16: 4 KB row segments, 8 rows per lane");
+    CHECK(tile_plan(8, 3, 4, 512, true, large, 0, 8).lpr == 512, "n = 8: the whole workgroup on one row");
     if (failures) return 1;
     std::printf("launch plan ok\n");
     return 0;

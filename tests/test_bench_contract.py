@@ -57,6 +57,8 @@ def test_json_line_on_the_small_workload():
     ["--workload", "2", "--degree", "5"],
     ["--workload", "4", "--overlap"],
     ["--workload", "4", "--graph", "--no-consensus"],
+    ["--workload", "2", "--two-rings"],
+    ["--workload", "2", "--g-apart"],
 ])
 def test_variants_run_and_report(flags):
     """Every benchmark variant runs to completion and prints one well-formed line."""
@@ -64,8 +66,33 @@ def test_variants_run_and_report(flags):
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--steps", "3", "--warmup", "1",
-                        "--no-cpu-baseline"] + flags, capture_output=True, text=True, timeout=600)
+                        "--no-cpu-baseline", "--no-extra-legs"] + flags, capture_output=True, text=True, timeout=600)
     assert p.returncode == 0, p.stderr[-2000:]
     r = json.loads(p.stdout.strip())
     assert r["value"] > 1e10 and 0.2 < r["roofline"]["frac"] < 1.0, r
     assert r["config"]["workload"].startswith("cfg" + flags[1])
+
+
+@pytest.mark.gpu
+def test_default_form_reports_the_legs_it_is_read_against():
+    """Without flags the line also carries the same step in place and on dense arrays, the reference streams
+    (read-only, write-only, x + a g in the step kernel's access pattern) and the runtime's device copy."""
+    torch = pytest.importorskip("torch")
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", "2", "--steps", "3", "--warmup", "1"],
+                       capture_output=True, text=True, timeout=600)
+    assert p.returncode == 0, p.stderr[-2000:]
+    r = json.loads(p.stdout.strip())
+    for key in ("pitched_out_of_place", "pitched_in_place", "dense_out_of_place", "dense_in_place"):
+        leg = r["legs"][key]
+        assert 0.2 < leg["frac"] < 1.0 and leg["avg_launch_ms"] > 0 and leg["workload"].startswith("cfg2"), (key, leg)
+    for block in ("reference_streams", "reference_streams_dense"):
+        for key in ("read_x_and_g", "write_x_out", "axpy_x_plus_a_g"):
+            assert 0.2 < r[block][key]["frac"] < 1.0, (block, key, r[block][key])
+    assert r["reference_streams"]["axpy_x_plus_a_g"]["bytes_per_element"] == 12
+    assert r["device_copy"]["achieved_GBps"] > 0
+    assert r["roofline"]["target_frac"] == 0.80 and r["roofline"]["target_met"] == (r["roofline"]["frac"] >= 0.80)
+    sp = r["cpu_baseline_sparse"]
+    assert sp["single_thread"]["value"] > 0 and sp["all_cores"]["cores"] >= 1
+    assert r["cpu_baseline"]["kind"] == "oracle"

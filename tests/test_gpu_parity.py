@@ -876,3 +876,28 @@ def test_two_streams_gathering_distances_are_serialised(psgd):
             assert abs(got[r, i] - c_want) <= REL * c_want, (r, i, got[r, i], c_want)
             assert abs(sep[r, i] - c_want) <= REL * c_want, (r, i, sep[r, i], c_want)
     assert psgd.device_status() == 0
+
+
+@pytest.mark.parametrize("n,d", [(3, 8), (8, 4100), (16, 1_600_004)])
+@pytest.mark.parametrize("gkind", ["f32", "bf16"])
+def test_reference_streams_do_what_they_say(psgd, n, d, gkind):
+    """The benchmark's reference streams are measurement support, but their rates are only worth comparing
+    with the step's if they move the bytes they claim: the write stream fills X_out, the x + a g stream
+    equals the oracle's update with the identity as mixing matrix and lr = -a, the read stream changes nothing."""
+    X = inp.host_normal_f32((n, d), 1.0, 500 + n)
+    G = (inp.host_normal_bf16_bits if gkind == "bf16" else inp.host_normal_f32)((n, d), 0.5, 600 + n)
+    Xd = dev(X)
+    Gd = bits_dev(G) if gkind == "bf16" else dev(G)
+    out = torch.full_like(Xd, float("nan"))
+    psgd.reference_stream(psgd.REF_READ, Xd, out, Gd)
+    torch.cuda.synchronize()
+    assert torch.isnan(out).all() and np.array_equal(Xd.cpu().numpy(), X)
+    psgd.reference_stream(psgd.REF_WRITE, Xd, out, Gd, a=0.25)
+    torch.cuda.synchronize()
+    assert (out == 0.25).all()
+    psgd.reference_stream(psgd.REF_AXPY, Xd, out, Gd, a=0.5)
+    torch.cuda.synchronize()
+    want = orc.mix_step(X, G, np.eye(n), -0.5)
+    assert_close(out.cpu().numpy(), want)
+    with pytest.raises(psgd.PsgdError):
+        psgd.reference_stream(psgd.REF_AXPY, Xd, Xd, Gd)          # output over an input

@@ -686,6 +686,55 @@ def test_densify_planted_mistakes_are_caught():
         assert _pins_for_densify(m) > 0, name
 
 
+# ------------------------------------------------------------------ sparse C form of the update
+def test_sparse_step_typed_out_example():
+    """Sec. 2, Eq. 2 on the asymmetric 3/4-1/4 table, by hand: learner 0 <- 3/4 x_0 + 1/4 x_2, and so on,
+    minus lr times the gradient (lr = 1/2, exact in fp32)."""
+    nbr = np.array([[0, 2], [1, 0], [2, 1]], dtype=np.int32)
+    w = np.array([[0.75, 0.25]] * 3, dtype=np.float32)
+    X = np.array([[1.0, 10.0], [2.0, 20.0], [4.0, 40.0]], dtype=np.float32)
+    G = np.array([[2.0, 0.0], [0.0, 4.0], [-2.0, 8.0]], dtype=np.float32)
+    want = np.array([[1.75 - 1.0, 17.5], [1.75, 17.5 - 2.0], [3.5 + 1.0, 35.0 - 4.0]])
+    assert np.array_equal(orc.sparse_mix_step(X, G, nbr, w, 0.5), want)
+    assert np.array_equal(orc.sparse_mix_step(X, G, nbr, w, 0.5, threads=4), want)
+
+
+@pytest.mark.parametrize("n,deg,d", [(1, 3, 5), (2, 3, 9), (5, 1, 4097), (8, 3, 10000), (16, 5, 8200), (64, 3, 5000)])
+@pytest.mark.parametrize("gkind", ["f32", "bf16"])
+def test_sparse_step_equals_dense_oracle(n, deg, d, gkind):
+    """The gather-add in C against the dense product T^T X - lr G (itself pinned above) on random asymmetric
+    tables and on the ring tables, one and several threads, ragged column counts."""
+    rng = np.random.default_rng(100 * n + deg)
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    G = rng.standard_normal((n, d)).astype(np.float32)
+    if gkind == "bf16":
+        G = inp.f32_to_bf16_bits(G)
+    if deg == 3:
+        nbr, w = orc.neighbour_table(orc.TOPO_RAND_RING, n, 5, n)
+    else:
+        nbr = np.stack([rng.permutation(n) for _ in range(deg)], axis=1).astype(np.int32)
+        c = rng.random(deg)
+        w = np.tile((c / c.sum()).astype(np.float32), (n, 1))
+    want = orc.mix_step(X, G, orc.densify(nbr, w), 0.3)
+    for threads in (1, 3):
+        got = orc.sparse_mix_step(X, G, nbr, w, 0.3, threads=threads)
+        assert np.allclose(got, want, rtol=0, atol=1e-14 * max(1.0, np.abs(want).max()))
+    assert abs(orc.sparse_consensus_dist(want, threads=2) - orc.consensus_dist(want)) <= 1e-12 * orc.consensus_dist(want) + 1e-300
+
+
+def test_sparse_step_planted_mistake_is_caught():
+    """Reading the table the other way round (learner i SENDS to nbr[i, s]) is the transposed matrix: the
+    typed-out example above tells them apart."""
+    nbr = np.array([[0, 2], [1, 0], [2, 1]], dtype=np.int32)
+    w = np.array([[0.75, 0.25]] * 3, dtype=np.float32)
+    X = np.array([[1.0, 10.0], [2.0, 20.0], [4.0, 40.0]], dtype=np.float32)
+    Z = np.zeros_like(X)
+    right = orc.sparse_mix_step(X, Z, nbr, w, 0.0)
+    wrong = orc.mix_step(X, Z, orc.densify(nbr, w).T, 0.0)
+    assert not np.array_equal(right, wrong)
+    assert np.array_equal(right, np.array([[1.75, 17.5], [1.75, 17.5], [3.5, 35.0]]))
+
+
 def test_golden_tables_still_match_oracle(golden_dir):
     """The frozen tables were written by the oracle; a drift in its generator shows here."""
     with open(os.path.join(golden_dir, "mixing_tables.txt")) as f:
