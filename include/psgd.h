@@ -113,10 +113,12 @@ int psgd_build_mixing_device(int topology, int n, uint64_t seed, uint64_t* step_
  * Per element, in fp32 and in this order: acc = w0 * x_self; acc = fma(w1, x_left, acc);
  * acc = fma(w2, x_right, acc); out = fma(-lr, g, acc).
  *
- * Enqueues two kernels on `stream` and returns without waiting: the table lives in device
- * memory, so only the device can tell whether it is one ring (every table of Sec. 3 is) or a
- * general 3-slot table; the ring-walk kernel and the tiled kernel both classify it, and the one
- * the table does not belong to exits at once.  Errors: PSGD_EINVAL;
+ * Enqueues its work on `stream` and returns without waiting.  The table lives in device memory,
+ * so only the device can tell whether it is one ring (every table of Sec. 3 is) or a general
+ * 3-slot table.  Short rows: one kernel that holds both paths.  Long rows (from about 1.5 M
+ * columns): two kernels, the ring walk and behind it the tiled kernel, each shaped for its own
+ * path; both classify the table and the one it does not belong to exits at once.
+ * Errors: PSGD_EINVAL;
  * PSGD_EALIAS (X_out partially overlaps X, X_out overlaps G, or X_out == X with
  * delay_mode 1); PSGD_EALIGN (X, X_out, G not 4-byte aligned); PSGD_EHIP.  A table entry
  * outside [0, n) cannot be seen by the host: the kernel then writes nothing and raises the
@@ -149,9 +151,10 @@ int psgd_mix_step_bf16g(const float* X, float* X_out, const uint16_t* G_bf16,
  * Uses the same per-device buffer of partial sums as psgd_consensus_dist_async (allocated by
  * the first such call on a device, which therefore must not happen while `stream` is being
  * captured into a graph: PSGD_EHIP).  Calls on different streams of one device share it; the
- * library orders them on the device (the later call's stream waits for the earlier call's last
- * kernel), so they serialise instead of racing.  Work captured into graphs is exempt: graph
- * launches that use the buffer must be ordered by the caller.
+ * library orders them on the device (a call that comes on another stream than the previous one
+ * makes its stream wait for everything enqueued so far on that previous stream), so they
+ * serialise instead of racing.  Work captured into graphs is exempt: graph launches that use
+ * the buffer must be ordered by the caller.
  * All other arguments, modes and errors are those of psgd_mix_step; d = 0 writes 0.
  */
 int psgd_mix_step_cd(const float* X, float* X_out, const float* G,

@@ -1161,8 +1161,8 @@ __global__ __launch_bounds__(kThreads) void build_mixing_kernel(int randomize, i
 struct DeviceInfo {
     int cus = 0;
     double* partials = nullptr;        // hipMalloc'ed on first use: kMaxGrid partials + 1 result slot
-    hipEvent_t partials_idle = nullptr;  // recorded behind the last kernel that read `partials`
-    hipStream_t partials_stream = nullptr;  // the stream that event was recorded on
+    hipEvent_t partials_idle = nullptr;     // recorded on the previous user's stream when another stream takes over
+    hipStream_t partials_stream = nullptr;  // the stream (not under capture) that used `partials` last
     bool partials_used = false;
     double* static_partials = nullptr;  // device address of ::scratch on this GPU (psgd_mix_step_cd_static)
 };
@@ -1204,12 +1204,18 @@ bool stream_is_capturing(hipStream_t s) {
 // The per-device partials buffer of the fused-distance and consensus calls, handed to work that is about
 // to be enqueued on `s`.  It is allocated on the first call on a device; allocation is not allowed while a
 // stream is being captured, so a first call made under capture is refused with an explanation instead of
-// invalidating the capture.  All calls on a device share the buffer: when the previous user enqueued on
-// another stream, `s` is made to wait (on the device, not on the host) for that user's last kernel, so two
-// streams that both gather a distance are serialised instead of racing.  Streams under capture are left
+// invalidating the capture.  All calls on a device share the buffer.  As long as they come on one stream the
+// stream orders them and nothing is done here (no runtime call at all: short launches are bound by host time).
+// When a call arrives on another stream than the previous one, an event is recorded behind everything enqueued
+// so far on the previous stream and the new stream is made to wait for it (on the device, not on the host), so
+// two streams that both gather a distance are serialised instead of racing.  Streams under capture are left
 // alone: the order of graph launches is the caller's.
 int acquire_partials(DeviceInfo* di, hipStream_t s, double** out) {
     std::lock_guard<std::mutex> lock(g_dev_mutex);
+    if (di->partials && di->partials_used && di->partials_stream == s) {
+        *out = di->partials;
+        return PSGD_OK;
+    }
     const bool capturing = stream_is_capturing(s);
     if (!di->partials) {
         if (capturing)
@@ -1224,24 +1230,27 @@ int acquire_partials(DeviceInfo* di, hipStream_t s, double** out) {
             return hip_fail(e, "hipEventCreateWithFlags");
         }
     }
-    if (!capturing && di->partials_used && di->partials_stream != s) {
-        const hipError_t e = hipStreamWaitEvent(s, di->partials_idle, 0);
-        if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent(partials)");
-    }
     *out = di->partials;
-    return PSGD_OK;
-}
-
-// Called after the last kernel that reads the partials has been enqueued on `s`.
-int release_partials(DeviceInfo* di, hipStream_t s) {
-    std::lock_guard<std::mutex> lock(g_dev_mutex);
-    if (stream_is_capturing(s)) return PSGD_OK;
-    const hipError_t e = hipEventRecord(di->partials_idle, s);
-    if (e != hipSuccess) return hip_fail(e, "hipEventRecord(partials)");
+    if (capturing) return PSGD_OK;                // captured work: ordered by whoever launches the graphs
+    if (di->partials_used && !stream_is_capturing(di->partials_stream)) {
+        // another stream used the buffer last: wait for all it has been given so far.  If that stream no longer
+        // exists the record fails; its work may still be running, so the whole device is waited for instead.
+        hipError_t e = hipEventRecord(di->partials_idle, di->partials_stream);
+        if (e == hipSuccess) e = hipStreamWaitEvent(s, di->partials_idle, 0);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            e = hipDeviceSynchronize();
+            if (e != hipSuccess) return hip_fail(e, "hipDeviceSynchronize(partials)");
+        }
+    }
     di->partials_stream = s;
     di->partials_used = true;
     return PSGD_OK;
 }
+
+// Called after the last kernel that reads the partials has been enqueued on `s` (nothing to do: the next user
+// on another stream records its own event behind this work).
+int release_partials(DeviceInfo*, hipStream_t) { return PSGD_OK; }
 
 // Device address of the static scratch array on the current GPU, looked up once per device.
 int static_partials(DeviceInfo* di, double** out) {
