@@ -42,6 +42,7 @@ constexpr int kTileThreads = 512;    // workgroup of the tiled path on long rows
 constexpr int kUnroll = 8;           // rows whose loads are in flight together per lane
 using plan::kMaxGrid;                // upper bound on persistent workgroups (partials buffer sizing)
 constexpr int kGridPerCu = 4;        // persistent workgroups per compute unit (16 waves per CU)
+constexpr int kXcds = 8;             // accelerator dies of an MI355X: consecutive workgroups go to consecutive dies
 // LDS a workgroup may ask for: a compute unit has 160 KB.  The large lockstep workgroup is alone on its CU
 // and may take nearly all of it; the small one leaves room for four per CU unless the table needs more.
 constexpr size_t kLdsCapLarge = 160 * 1024 - 1024;
@@ -618,7 +619,7 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
     double* comb = reinterpret_cast<double*>(tiles + 2 * tile_bytes);   // [T / 64][lpr][VEC], CD only
     const int64_t ntiles = (ncg + lpr - 1) / lpr;
     const int64_t step = gridDim.x;
-    int64_t t = blockIdx.x;
+    int64_t t = plan::die_contiguous_slot(blockIdx.x, gridDim.x, kXcds);   // the first of tiles t, t + step, ...
     if (t >= ntiles) return 0.0;                             // uniform: the whole workgroup has nothing to do
     double total = 0.0;
     TileStats<VEC> st;
@@ -779,7 +780,9 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
 struct Sweeps {
     int64_t count, chunk;
     // first column group of this workgroup in sweep sw
-    __device__ __forceinline__ int64_t base(int64_t sw) const { return (sw * gridDim.x + blockIdx.x) * chunk; }
+    __device__ __forceinline__ int64_t base(int64_t sw) const {
+        return (sw * gridDim.x + plan::die_contiguous_slot(blockIdx.x, gridDim.x, kXcds)) * chunk;
+    }
 };
 // Computed by the launcher (the device would pay two 64-bit divisions per lane for it).
 inline Sweeps make_sweeps(int64_t ncg, int grid, int threads) {

@@ -5,6 +5,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <initializer_list>
+#include <vector>
 
 #include "psgd_internal.h"
 
@@ -59,6 +60,21 @@ int main() {
     for (int64_t ncg : rows)
         for (int g : grids)
             for (int t : threads) check_cover(ncg, g, t);
+    // the die-contiguous mapping permutes the ranges of a sweep among the workgroups: a bijection, and the
+    // workgroups of one die (b, b + 8, ...) take neighbouring ranges
+    for (int grid : {1, 7, 8, 16, 255, 256, 304, 1024}) {
+        std::vector<int> seen(grid, 0);
+        for (int b = 0; b < grid; ++b) {
+            const int64_t s = die_contiguous_slot(b, grid, 8);
+            CHECK(s >= 0 && s < grid, "grid %d: slot %lld of workgroup %d", grid, (long long)s, b);
+            if (s >= 0 && s < grid) ++seen[s];
+        }
+        for (int i = 0; i < grid; ++i) CHECK(seen[i] == 1, "grid %d: range %d taken %d times", grid, i, seen[i]);
+        if (grid % 8 == 0 && grid >= 16)
+            CHECK(die_contiguous_slot(8, grid, 8) == die_contiguous_slot(0, grid, 8) + 1, "grid %d: die neighbours", grid);
+        else if (grid % 8 != 0)
+            CHECK(die_contiguous_slot(grid - 1, grid, 8) == grid - 1, "grid %d: identity expected", grid);
+    }
     // workload 5 on 256 compute units: 128 sweeps of 768-group chunks, the last range 64 groups long
     const SweepPlan w5 = sweep_plan(25000000, 256, 768);
     CHECK(w5.count == 128 && w5.chunk == 768, "workload 5 plan %lld x %lld", (long long)w5.count, (long long)w5.chunk);
