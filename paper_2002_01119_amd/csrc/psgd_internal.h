@@ -76,7 +76,8 @@ inline SweepPlan sweep_plan(int64_t ncg, int grid, int threads) {
 // LDS of the tiled path (tables that are not one ring): the slot table (8 bytes per slot), TWO tile buffers of
 // n rows x lpr lanes x vec floats (the next tile is staged while the current one is read), and, when the
 // consensus distance is gathered in the same pass, the merge slots of the column sums: one double per column
-// and per wavefront (lpr <= 64: row groups inside a wavefront merge by shuffles) or per row group (lpr > 64).
+// and per wavefront (lpr <= 64: row groups inside a wavefront merge by shuffles) or per row group (lpr > 64),
+// plus a float per slot where row groups are whole wavefronts (lpr >= 64: each keeps its own pivot).
 // `lpr`, the lanes that share a row, is the largest power of two <= threads for which all of it, plus `base`
 // bytes the kernel keeps for itself, fits `cap`; rows wider than a wavefront (lpr > 64) are only taken while a
 // lane still gets at most `rows_per_batch` rows, which is what few learners need to keep enough bytes in flight
@@ -93,7 +94,7 @@ inline TilePlan tile_plan(int n, int deg, int vec, int threads, bool cd, size_t 
         if (p.lpr > 64 && (n + nrg - 1) / nrg > rows_per_batch) continue;
         const int slots = p.lpr <= 64 ? threads / 64 : nrg;
         p.tile_bytes = (((size_t)n * p.lpr * vec * 4) + 15) & ~(size_t)15;
-        p.comb_bytes = cd ? (size_t)slots * p.lpr * vec * 8 : 0;
+        p.comb_bytes = cd ? (size_t)slots * p.lpr * vec * (p.lpr >= 64 ? 12 : 8) : 0;   // + a float pivot per slot for whole-wavefront rows
         p.total = base + p.tab_bytes + 2 * p.tile_bytes + p.comb_bytes;
         if (p.total <= cap) return p;
     }

@@ -441,7 +441,7 @@ __device__ __forceinline__ void ring_walk(const float* xc, float* oc, const GT* 
 template <int T> struct TileShape {
     static constexpr int RB = T > 256 ? 8 : 2;   // rows per lane and batch
     static constexpr int SB = T > 256 ? 3 : 2;   // rows whose slot chains advance together (two slots per trip each);
-                                                 // 3 x 3 = the pivot row + 8 rows when the distance is gathered
+                                                 // more rows at once cost registers and ran slower (4: -1 to -6 %)
 };
 
 // Per-lane state of the tiled path that does not change from tile to tile.
@@ -449,6 +449,7 @@ template <int VEC>
 struct TileCtx {
     const TileSlot* tab;
     int n, deg, lpr, lane, rg, nrg;
+    int rows_each, rows_more;   // n = rows_each * nrg + rows_more: row group q has rows_each (+ 1 if q < rows_more) rows
     int tlane;   // the lane's column inside the tile (lane, or the last valid one for a lane beyond the ragged end)
     float neg_lr;
 };
@@ -475,12 +476,15 @@ struct TileStats {
 // early stay in flight: the compiler counts outstanding memory operations to wait for exactly the ones it
 // needs, and a load or store that may or may not have been issued makes that count unknown, upon which it
 // waits for all of them.
-template <int VEC, bool CD, int RB, int SB, bool CLAMP, typename GR>
+//
+// OWNPIV (with CLAMP and CD): no extra item; the lane's first own output is its pivot, and the merge at the end
+// of the tile brings the row groups' sums to one common pivot (tile_finish_own).
+template <int VEC, bool CD, int RB, int SB, bool CLAMP, bool OWNPIV, typename GR>
 __device__ __forceinline__ void tile_rows(const TileCtx<VEC>& c, const typename Cols<VEC>::T* cur, int b, const GR (&g)[RB],
                                           GR g0, bool with_pivot, bool active, float* out_col, int64_t ldo,
                                           TileStats<VEC>& st) {
     typedef typename Cols<VEC>::T V;
-    constexpr int P = CD ? 1 : 0, ITEMS = RB + P;
+    constexpr int P = (CD && !OWNPIV) ? 1 : 0, ITEMS = RB + P;
 #pragma unroll
     for (int j0 = 0; j0 < ITEMS; j0 += SB) {
         const TileSlot* tp[SB];
@@ -490,7 +494,7 @@ __device__ __forceinline__ void tile_rows(const TileCtx<VEC>& c, const typename 
 #pragma unroll
         for (int i = 0; i < SB; ++i) {
             const int j = j0 + i;
-            const bool piv = CD && j == 0;
+            const bool piv = P && j == 0;
             row[i] = piv ? 0 : c.rg + (b * RB + (j - P)) * c.nrg;
             ok[i] = j < ITEMS && active && (piv ? with_pivot : row[i] < c.n);
             if (CLAMP) {
@@ -537,12 +541,13 @@ __device__ __forceinline__ void tile_rows(const TileCtx<VEC>& c, const typename 
 #pragma unroll
         for (int i = 0; i < SB; ++i) {
             const int j = j0 + i;
-            if (CD && j == 0) {
+            if (P && j == 0) {
                 if (CLAMP || ok[i]) pivot_of(vfma(c.neg_lr, widen_g(g0), acc[i]), st.piv);
             } else if (j < ITEMS) {
                 if (CLAMP || ok[i]) {
                     const V out = vfma(c.neg_lr, widen_g(g[j - P < 0 ? 0 : j - P]), acc[i]);
                     st_x(out_col + (int64_t)row[i] * ldo, out);
+                    if (CD && OWNPIV && j == 0) pivot_of(out, st.piv);
                     if (CD && ok[i]) {
                         double o[VEC];
                         pivot_of(out, o);      // widen
@@ -595,6 +600,44 @@ __device__ __forceinline__ void tile_finish(const TileCtx<VEC>& c, double* comb,
     }
 }
 
+// The same for row groups that each measured against their own pivot p_q (their first output): with P = p_0,
+// D_q = p_q - P and m_q rows in group q,
+//     sum_i (o_i - P)   = sum_q (a_q + m_q D_q)
+//     sum_i (o_i - P)^2 = sum_q (sq_q + 2 D_q a_q + m_q D_q^2)
+// exactly; in fp64 the corrections are of the size of the sums themselves (every pivot is one of the outputs).
+// If all outputs of a column are equal every D_q is 0 and the distance comes out exactly 0.  Row groups are whole
+// wavefronts here (lpr >= 64): one slot per row group, a double for the sum and a float for the pivot.
+template <int VEC, int T>
+__device__ __forceinline__ void tile_finish_own(const TileCtx<VEC>& c, double* comb, float* combp, int live_cols,
+                                                TileStats<VEC>& st, double inv_n, double& total) {
+    const size_t mine = (size_t)(c.rg * c.lpr + c.lane) * VEC;
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+        comb[mine + k] = st.a[k];
+        combp[mine + k] = (float)st.piv[k];      // the pivot is an fp32 output: nothing is lost
+    }
+    total += st.sq;
+    lds_barrier();
+    // one lane per column (the tile has lpr * VEC of them, spread over the whole workgroup: a merge left to one
+    // wavefront would keep all the others waiting at the barrier below)
+    for (int idx = threadIdx.x; idx < live_cols * VEC; idx += T) {
+        const double p0 = (double)combp[idx];    // row group 0 owns row 0: its pivot is the common one
+        double at = 0.0, corr = 0.0;
+        for (int q = 0; q < c.nrg; ++q) {
+            const int m = c.rows_each + (q < c.rows_more ? 1 : 0);     // rows q, q + nrg, ... below n
+            if (m) {
+                const double md = (double)m;
+                const size_t at_q = (size_t)q * c.lpr * VEC + idx;
+                const double aq = comb[at_q], dq = (double)combp[at_q] - p0;
+                at += fma(md, dq, aq);
+                corr += dq * fma(md, dq, 2.0 * aq);
+            }
+        }
+        total += corr - at * at * inv_n;
+    }
+    lds_barrier();                                     // the merge slots are free again
+}
+
 template <int VEC, typename GT, bool CD, int T>
 __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ G, const TileSlot* tab, char* tiles,
                             int n, int deg, Pitch ld, int64_t ncg, float neg_lr, int lpr, double inv_n) {
@@ -610,6 +653,8 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
     c.lane = c.tlane = threadIdx.x % lpr;
     c.rg = threadIdx.x / lpr;
     c.nrg = T / lpr;
+    c.rows_each = n / c.nrg;
+    c.rows_more = n % c.nrg;
     c.neg_lr = neg_lr;
     const int lane = c.lane, rg = c.rg, nrg = c.nrg;
     const int nb = ((n + nrg - 1) / nrg + RB - 1) / RB;      // batches per tile: the same for every lane
@@ -687,7 +732,7 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
                 xs[u] = ld_x(X + (int64_t)r * ld.x + col, tag);
             }
         };
-        auto ld_gs = [&](int64_t tile, GR (&g)[RB], GR& gp) {
+        auto ld_gs = [&](int64_t tile, GR (&g)[RB]) {
             const int64_t col = cge_of(tile) * VEC;
 #pragma unroll
             for (int u = 0; u < RB; ++u) {
@@ -695,24 +740,24 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
                 r = r < last_row ? r : last_row;
                 g[u] = ld_g_raw(G + (int64_t)r * ld.g + col, tag);
             }
-            if (CD) gp = ld_g_raw(G + col, tag);
         };
+        float* combp = reinterpret_cast<float*>(comb + (size_t)nrg * lpr * VEC);   // pivots, behind the sums
         V xa[RB], xb[RB];
-        GR ga[RB], gb[RB], g0a = {}, g0b = {};
+        GR ga[RB], gb[RB];
         ld_xs(t + step, xa);
-        ld_gs(t, ga, g0a);
+        ld_gs(t, ga);
         lds_barrier();
         // one tile: issue X of tile t + 2 step into `xi` and gradients of t + step into `gi`, compute tile t with
         // `gu`, stage X of tile t + step (issued one tile ago into `xw`) into the other buffer
-#define PSGD_TILE_ROUND(xw, xi, gu, gi, g0u, g0i)                                                                        \
+#define PSGD_TILE_ROUND(xw, xi, gu, gi)                                                                                  \
     do {                                                                                                                 \
         ld_xs(t + 2 * step, xi);                                                                                         \
-        ld_gs(t + step, gi, g0i);                                                                                        \
+        ld_gs(t + step, gi);                                                                                             \
         const int64_t cge = cge_of(t);                                                                                   \
         const bool active = t * lpr + lane < ncg;                                                                        \
         c.tlane = (int)(cge - t * lpr);                                                                                  \
         if (CD) st.reset();                                                                                              \
-        tile_rows<VEC, CD, RB, SB, true>(c, cur, 0, gu, g0u, true, active, Xout + cge * VEC, ld.o, st);                  \
+        tile_rows<VEC, CD, RB, SB, true, true>(c, cur, 0, gu, GR{}, false, active, Xout + cge * VEC, ld.o, st);          \
         {                                                                                                                \
             const int lane_n = (int)(cge_of(t + step) - (t + step) * lpr);   /* negative beyond the last tile */          \
             _Pragma("unroll") for (int u = 0; u < RB; ++u) {                                                             \
@@ -721,16 +766,21 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
                 if (lane_n >= 0) nxt[r * lpr + lane_n] = xw[u];                                                          \
             }                                                                                                            \
         }                                                                                                                \
-        tile_finish<VEC, CD, T>(c, comb, active, st, inv_n, total);                                                      \
+        if (CD) {                                                                                                        \
+            const int64_t left = ncg - t * lpr;                       /* column groups of this tile (uniform) */         \
+            tile_finish_own<VEC, T>(c, comb, combp, (int)(left < lpr ? left : lpr), st, inv_n, total);                   \
+        } else {                                                                                                         \
+            lds_barrier();                                                                                               \
+        }                                                                                                                \
         V* sw_ = cur;                                                                                                    \
         cur = nxt;                                                                                                       \
         nxt = sw_;                                                                                                       \
         t += step;                                                                                                       \
     } while (0)
         for (;;) {
-            PSGD_TILE_ROUND(xa, xb, ga, gb, g0a, g0b);
+            PSGD_TILE_ROUND(xa, xb, ga, gb);
             if (t >= ntiles) break;
-            PSGD_TILE_ROUND(xb, xa, gb, ga, g0b, g0a);
+            PSGD_TILE_ROUND(xb, xa, gb, ga);
             if (t >= ntiles) break;
         }
 #undef PSGD_TILE_ROUND
@@ -758,7 +808,7 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
                 load_g(rg, tn, 0, gn);
                 if (CD && live(tn)) g0n = ld_g_raw(G + col_of(tn), tag);
             }
-            tile_rows<VEC, CD, RB, SB, false>(c, cur, b, gcur, g0, b == 0, active, Xout + col_of(t), ld.o, st);
+            tile_rows<VEC, CD, RB, SB, false, false>(c, cur, b, gcur, g0, b == 0, active, Xout + col_of(t), ld.o, st);
             stash(rg, tn, b, nxt, xs);
 #pragma unroll
             for (int u = 0; u < RB; ++u) gcur[u] = gn[u];

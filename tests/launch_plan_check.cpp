@@ -122,7 +122,7 @@ int main() {
                             CHECK(p.tab_bytes >= (size_t)n * deg * 8 && p.tab_bytes % 16 == 0, "slot table size");
                             CHECK(p.tile_bytes >= (size_t)n * p.lpr * vec * 4 && p.tile_bytes % 16 == 0, "tile size");
                             const size_t slots = p.lpr <= 64 ? threads / 64 : nrg;
-                            CHECK(p.comb_bytes == (cd ? slots * p.lpr * vec * 8 : 0), "merge slots");
+                            CHECK(p.comb_bytes == (cd ? slots * p.lpr * vec * (p.lpr >= 64 ? 12 : 8) : 0), "merge slots");
                             CHECK(p.total == p.tab_bytes + 2 * p.tile_bytes + p.comb_bytes, "total");
                         }
         }
