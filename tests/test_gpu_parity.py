@@ -901,3 +901,60 @@ def test_reference_streams_do_what_they_say(psgd, n, d, gkind):
     assert_close(out.cpu().numpy(), want)
     with pytest.raises(psgd.PsgdError):
         psgd.reference_stream(psgd.REF_AXPY, Xd, Xd, Gd)          # output over an input
+
+
+# ------------------------------------------------------------------------- tiled kernel on long rows
+def _two_rings_table(n):
+    """The even and the odd learners on two disjoint rings: 3 slots, locally consistent, not ONE ring."""
+    idx = np.arange(n)
+    nbr = np.stack([idx, (idx - 2) % n, (idx + 2) % n], axis=1).astype(np.int32)
+    return nbr, np.tile(np.asarray([0.5, 0.25, 0.25], dtype=np.float32), (n, 1))
+
+
+@pytest.mark.parametrize("n,d", [(64, 1_600_004), (64, 1_572_867), (128, 1_600_004), (33, 1_700_004), (8, 1_800_004)])
+@pytest.mark.parametrize("kind", ["two_rings", "deg5", "deg13"])
+@pytest.mark.parametrize("gkind", ["f32", "bf16"])
+def test_tiled_kernel_long_rows_every_element(psgd, n, d, kind, gkind):
+    """Rows long enough for the large-workgroup tiled kernel (tiles two ahead in registers for n <= 64, one
+    ahead for n = 128, wide rows for n = 8; d not a multiple of 4 takes one column per lane): every element
+    and the fused distance against the oracle, out of place and in place, ragged last tile included."""
+    rng = np.random.default_rng(n + d % 1000)
+    if kind == "two_rings":
+        if n % 2:
+            pytest.skip("two rings need an even learner count")
+        nbr, w = _two_rings_table(n)
+    else:
+        nbr, w = _perm_sum_table(n, 5 if kind == "deg5" else 13, rng)
+    X = inp.host_normal_f32((n, d), 1.0, 700 + n)
+    G = inp.host_normal_f32((n, d), 0.5, 710 + n)
+    if gkind == "bf16":
+        G = inp.f32_to_bf16_bits(G)
+    want = orc.mix_step(X, G, orc.densify(nbr, w), 0.2)
+    got, c = run_step_cd(psgd, X, G, nbr, w, 0.2)
+    assert_close(got, want)
+    c_ref = orc.consensus_dist(got)
+    assert abs(c - c_ref) <= REL * c_ref
+    got_ip, c_ip = run_step_cd(psgd, X, G, nbr, w, 0.2, in_place=True)
+    assert np.array_equal(got_ip.view(np.uint32), got.view(np.uint32)) and c_ip == c
+    got_plain = run_step(psgd, X, G, nbr, w, 0.2)                # the build without the distance
+    assert np.array_equal(got_plain.view(np.uint32), got.view(np.uint32))
+    assert psgd.device_status() == 0
+
+
+@pytest.mark.parametrize("n", [16, 64])
+def test_tiled_kernel_long_rows_distance_corner_cases(psgd, n):
+    """The row groups of the large tiled kernel each measure against their own pivot and the merge brings
+    them to a common one: replicas far from the origin and close together must still give the distance to
+    1e-6, and identical outputs must give exactly 0."""
+    d = 1_600_004
+    nbr, w = _two_rings_table(n)
+    base = inp.host_normal_f32((1, d), 100.0, 3)
+    X = (np.tile(base, (n, 1)) + inp.host_normal_f32((n, d), 1e-3, 4)).astype(np.float32)
+    G = np.full((n, d), 7.0, np.float32)
+    got, c = run_step_cd(psgd, X, G, nbr, w, 1.0)
+    assert_close(got, orc.mix_step(X, G, orc.densify(nbr, w), 1.0))
+    c_ref = orc.consensus_dist(got)
+    assert abs(c - c_ref) <= REL * c_ref
+    Xe = np.tile(base, (n, 1)).astype(np.float32)
+    got, c = run_step_cd(psgd, Xe, G, nbr, w, 0.5)
+    assert np.array_equal(got, np.tile(got[0], (n, 1))) and c == 0.0
