@@ -10,13 +10,16 @@
 //     the ring in position order holding three consecutive rows in registers, so each
 //     neighbour read is a register move, not a memory access, and the update may run in
 //     place because a row is only written after its old value is in registers;
-//   * any other table goes through an [n x columns] tile in LDS, loaded completely before
-//     the first write, which gives the same two properties at the price of a barrier.
-// The 3-slot table is staged in LDS once per workgroup; workgroups are persistent and
-// stride over the column groups, so that cost is paid once per launch.  On long rows the
-// workgroup is large (768 lanes) and its wavefronts sweep the rows in lockstep, a barrier per
-// batch of rows: the HBM then sees one 12 KB burst per row instead of twelve separate 1 KB
-// requests, which is worth 1-3 % of the peak for kernels that write.
+//   * any other table goes through [n x columns] tiles in LDS (a neighbour read is an LDS read), double
+//     buffered, with the next tiles travelling from HBM through registers while the current one is
+//     computed; a tile is complete in LDS before its first output is stored, so this path too may
+//     run in place.
+// Tables live in device memory and are validated and classified (one ring or not) by the kernels.
+// Workgroups are persistent, so table staging is paid once per launch.  On long rows the workgroups are
+// large (768 lanes for the ring walk, 512 for the tiled path), one per compute unit; the ring walk's
+// wavefronts sweep the rows in lockstep, a barrier per batch of rows: the HBM then sees one 12 KB burst
+// per row instead of twelve separate 1 KB requests, which is worth 1-3 % of the peak for kernels that
+// write.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
