@@ -309,38 +309,38 @@ def test_cfg5_bf16_gradients_full_size(psgd):
     torch.cuda.empty_cache()
 
 
-def test_cfg5_full_size_every_element_one_step(psgd):
-    """One step of workload 5 at full size, in the benchmark's launch (pitched rows, fused distance, large
-    lockstep workgroups, even split of the column groups over the persistent grid): EVERY one of the
-    6.4e9 outputs against the oracle.  The arrays are streamed back in column blocks (columns are
-    independent, so the oracle runs block by block); the sampled-column tests cannot see a mistake that
-    touches only the few columns at a workgroup's chunk boundary, this one does."""
+def _every_element_one_step(psgd, wl, step_index):
+    """One step of a workload at full size, in the benchmark's launch (pitched rows, fused distance, large
+    lockstep workgroups, even die-contiguous split of the column groups over the persistent grid): EVERY output
+    against the oracle.  The arrays are streamed back in column blocks (columns are independent, so the oracle
+    runs block by block); the sampled-column tests cannot see a mistake that touches only the few columns at a
+    workgroup's chunk boundary, this one does."""
     from paper_2002_01119_amd import placement as plc
-    wl = inp.workload(5)
     n, d = wl.n, wl.d
-    specs = [("X", torch.float32), ("Y", torch.float32), ("G", torch.bfloat16)]
+    gdt = torch.bfloat16 if wl.g_dtype == "bf16" else torch.float32
+    specs = [("X", torch.float32), ("Y", torch.float32), ("G", gdt)]
     total_mem = torch.cuda.mem_get_info()[1]
     views, pool, pitch = plc.pitched_layout(n, d, specs, int(0.65 * total_mem), "cuda:0", settle=False)
     X = inp.fill_normal_rows_(views["X"], wl.sigma_x, wl.seed_x)
     G = inp.fill_normal_rows_(views["G"], wl.sigma_g, wl.seed_g)
     Y = views["Y"]
     Y.fill_(float("nan"))
-    nbr, w = psgd.build_mixing(wl.topology, n, wl.seed_perm, 3)
-    onbr, ow = orc.neighbour_table(wl.topology, n, wl.seed_perm, 3)
+    nbr, w = psgd.build_mixing(wl.topology, n, wl.seed_perm, step_index)
+    onbr, ow = orc.neighbour_table(wl.topology, n, wl.seed_perm, step_index)
     assert np.array_equal(nbr, onbr) and np.array_equal(w.view(np.uint32), ow.view(np.uint32))
     T = orc.densify(nbr, w)
     cd = torch.zeros(1, dtype=torch.float64, device="cuda:0")
-    psgd.mix_step(X, Y, G, dev(nbr), dev(w), wl.lr, cdist_out=cd)
+    psgd.mix_step(X, Y, G, dev(nbr), dev(w), wl.lr, delay_mode=1 if wl.delay else 0, cdist_out=cd)
     torch.cuda.synchronize()
     assert psgd.device_status() == 0
-    block = 2_000_000
+    block = 128_000_000 // n
     max_err = max_out = 0.0
     err2 = out2 = 0.0
     c_sum = 0.0
     for lo in range(0, d, block):
         hi = min(lo + block, d)
         Xb = X[:, lo:hi].contiguous().cpu().numpy()
-        Gb = inp.bf16_tensor_bits(G[:, lo:hi])
+        Gb = inp.bf16_tensor_bits(G[:, lo:hi]) if wl.g_dtype == "bf16" else G[:, lo:hi].contiguous().cpu().numpy()
         Yb = Y[:, lo:hi].contiguous().cpu().numpy()
         want = orc.mix_step(Xb, Gb, T, wl.lr)
         diff = Yb - want                                   # fp32 - fp64 -> fp64; NaN if an output was never written
@@ -358,6 +358,18 @@ def test_cfg5_full_size_every_element_one_step(psgd):
     assert abs(cd.item() - c_sum) <= REL * c_sum
     del views, pool, X, Y, G
     torch.cuda.empty_cache()
+
+
+def test_cfg5_full_size_every_element_one_step(psgd):
+    """Workload 5 (n = 64, d = 1e8, bf16 G): all 6.4e9 outputs, 128 sweeps per workgroup, row offsets far
+    beyond 2^32."""
+    _every_element_one_step(psgd, inp.workload(5), 3)
+
+
+def test_cfg4_shape_every_element_one_step(psgd):
+    """Workload 4's shape (n = 128, d = 8e6, fp32 G, delay-by-one data flow): all 1.0e9 outputs; its rows need
+    10.2 sweeps' worth of column groups, the case the even split of the sweeps exists for."""
+    _every_element_one_step(psgd, inp.workload(4), 5)
 
 
 def test_cfg5_dense_layout_full_size(psgd):
