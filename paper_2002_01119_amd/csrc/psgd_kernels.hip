@@ -1058,6 +1058,48 @@ __global__ __launch_bounds__(kThreads) void consensus_partial_kernel(const float
     if (threadIdx.x == 0) partials[blockIdx.x] = bs;
 }
 
+// The same distance for long rows, in the form of the step kernels: one large workgroup per compute unit whose
+// wavefronts sweep the rows in lockstep batches, the column groups split evenly and die-contiguously over the
+// persistent grid.  A lane owns one column group per sweep; a lane beyond the ragged end shadows column group 0
+// and adds nothing.
+template <int VEC, int T>
+__global__ __launch_bounds__(T) void consensus_sweep_kernel(const float* __restrict__ X, int n, int64_t d, int64_t ldx,
+                                                            Sweeps sweeps, double* __restrict__ partials) {
+    typedef typename Cols<VEC>::T V;
+    const Cols<VEC> tag{};
+    __shared__ double lds_waves[T / 64];
+    const int64_t ncg = d / VEC;
+    const double inv_n = 1.0 / (double)n;
+    double total = 0.0;
+    for (int64_t sw = 0; sw < sweeps.count; ++sw) {
+        const int64_t base = sweeps.base(sw), cg = base + threadIdx.x;
+        if (base >= ncg) break;                                  // nothing left for this workgroup (uniform)
+        const int64_t end = base + sweeps.chunk < ncg ? base + sweeps.chunk : ncg;   // uniform
+        const bool act = cg < end;
+        const float* xc = X + (act ? cg : 0) * VEC;
+        double s[VEC], a[VEC], b[VEC];
+        pivot_of(ld_x(xc, tag), s);
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) a[k] = b[k] = 0.0;
+        int r = 1;
+        for (; r + kUnroll <= n; r += kUnroll) {
+            lockstep_barrier();
+            V xs[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) xs[u] = ld_x(xc + (int64_t)(r + u) * ldx, tag);
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) acc_diff<VEC>(a, b, xs[u], s);
+        }
+        for (; r < n; ++r) acc_diff<VEC>(a, b, ld_x(xc + (int64_t)r * ldx, tag), s);
+        if (act) {
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) total += b[k] - a[k] * a[k] * inv_n;
+        }
+    }
+    const double bs = block_sum<T>(total, lds_waves);
+    if (threadIdx.x == 0) partials[blockIdx.x] = bs;
+}
+
 // Fixed-order sum of the per-workgroup partials: lane t adds entries t, t+256, ... and the
 // 256 lane sums go through the same shuffle/LDS tree, so the result does not depend on
 // scheduling.
@@ -1679,11 +1721,23 @@ int consensus_enqueue(const float* X, int64_t ldx, int n, int64_t d, double* out
     const bool vec4 = (d % 4 == 0) && (ldx % 4 == 0) && aligned_to(X, 16);
     int grid = 0;
     if (d > 0) {
-        grid = persistent_grid(*di, vec4 ? d / 4 : d, 8);  // light kernel: 32 waves per CU
-        if (vec4)
-            hipLaunchKernelGGL(consensus_partial_kernel<4>, dim3(grid), dim3(kThreads), 0, s, X, n, d, ldx, partials);
-        else
-            hipLaunchKernelGGL(consensus_partial_kernel<1>, dim3(grid), dim3(kThreads), 0, s, X, n, d, ldx, partials);
+        const int64_t ncg = vec4 ? d / 4 : d;
+        if (long_rows(*di, ncg)) {
+            grid = persistent_grid(*di, ncg, 1, kRingThreads);
+            const Sweeps sw = make_sweeps(ncg, grid, kRingThreads);
+            if (vec4)
+                hipLaunchKernelGGL((consensus_sweep_kernel<4, kRingThreads>), dim3(grid), dim3(kRingThreads), 0, s, X, n, d,
+                                   ldx, sw, partials);
+            else
+                hipLaunchKernelGGL((consensus_sweep_kernel<1, kRingThreads>), dim3(grid), dim3(kRingThreads), 0, s, X, n, d,
+                                   ldx, sw, partials);
+        } else {
+            grid = persistent_grid(*di, ncg, 8);  // light kernel: 32 waves per CU
+            if (vec4)
+                hipLaunchKernelGGL(consensus_partial_kernel<4>, dim3(grid), dim3(kThreads), 0, s, X, n, d, ldx, partials);
+            else
+                hipLaunchKernelGGL(consensus_partial_kernel<1>, dim3(grid), dim3(kThreads), 0, s, X, n, d, ldx, partials);
+        }
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e, "consensus_partial_kernel");
     }
