@@ -482,14 +482,21 @@ struct TileStats {
 //
 // OWNPIV (with CLAMP and CD): no extra item; the lane's first own output is its pivot, and the merge at the end
 // of the tile brings the row groups' sums to one common pivot (tile_finish_own).
-template <int VEC, bool CD, int RB, int SB, bool CLAMP, bool OWNPIV, typename GR>
+//
+// `feed(j0)` runs in front of every group of SB rows: the caller's place for the loads of a later tile, so that
+// they enter the memory pipeline a few at a time between the rows' arithmetic instead of in one burst.
+struct NoFeed {
+    __device__ __forceinline__ void operator()(int) const {}
+};
+template <int VEC, bool CD, int RB, int SB, bool CLAMP, bool OWNPIV, typename GR, typename FEED = NoFeed>
 __device__ __forceinline__ void tile_rows(const TileCtx<VEC>& c, const typename Cols<VEC>::T* cur, int b, const GR (&g)[RB],
                                           GR g0, bool with_pivot, bool active, float* out_col, int64_t ldo,
-                                          TileStats<VEC>& st) {
+                                          TileStats<VEC>& st, const FEED& feed = FEED{}) {
     typedef typename Cols<VEC>::T V;
     constexpr int P = (CD && !OWNPIV) ? 1 : 0, ITEMS = RB + P;
 #pragma unroll
     for (int j0 = 0; j0 < ITEMS; j0 += SB) {
+        feed(j0);
         const TileSlot* tp[SB];
         bool ok[SB];
         int row[SB];
@@ -754,13 +761,25 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
         // `gu`, stage X of tile t + step (issued one tile ago into `xw`) into the other buffer
 #define PSGD_TILE_ROUND(xw, xi, gu, gi)                                                                                  \
     do {                                                                                                                 \
-        ld_xs(t + 2 * step, xi);                                                                                         \
-        ld_gs(t + step, gi);                                                                                             \
+        const int64_t colx = cge_of(t + 2 * step) * VEC, colg = cge_of(t + step) * VEC;                                  \
+        auto feed = [&](int j0) {                                                                                        \
+            __builtin_amdgcn_sched_barrier(0);                                                                           \
+            _Pragma("unroll") for (int i = 0; i < SB; ++i) {                                                             \
+                const int u = j0 + i;                                                                                    \
+                if (u < RB) {                                                                                            \
+                    int r = q + u * nrg;                                                                                 \
+                    r = r < last_row ? r : last_row;                                                                     \
+                    xi[u] = ld_x(X + (int64_t)r * ld.x + colx, tag);                                                     \
+                    gi[u] = ld_g_raw(G + (int64_t)r * ld.g + colg, tag);                                                 \
+                }                                                                                                        \
+            }                                                                                                            \
+            __builtin_amdgcn_sched_barrier(0);                                                                           \
+        };                                                                                                               \
         const int64_t cge = cge_of(t);                                                                                   \
         const bool active = t * lpr + lane < ncg;                                                                        \
         c.tlane = (int)(cge - t * lpr);                                                                                  \
         if (CD) st.reset();                                                                                              \
-        tile_rows<VEC, CD, RB, SB, true, true>(c, cur, 0, gu, GR{}, false, active, Xout + cge * VEC, ld.o, st);          \
+        tile_rows<VEC, CD, RB, SB, true, true>(c, cur, 0, gu, GR{}, false, active, Xout + cge * VEC, ld.o, st, feed);    \
         {                                                                                                                \
             const int lane_n = (int)(cge_of(t + step) - (t + step) * lpr);   /* negative beyond the last tile */          \
             _Pragma("unroll") for (int u = 0; u < RB; ++u) {                                                             \
