@@ -40,8 +40,10 @@ namespace {
 constexpr int kThreads = 256;        // 4 wavefronts of 64 lanes
 constexpr int kRingThreads = 768;    // workgroup of the step kernels on long rows (12 wavefronts in lockstep, one per CU;
                                      // 1024 lanes would leave the fused distance too few registers)
-constexpr int kTileThreads = 512;    // workgroup of the tiled path on long rows: 8 wavefronts, alone on its CU, so each may
-                                     // hold 256 registers (the next tile's rows travel through them)
+constexpr int kDeepThreads = 1024;   // workgroup of the tiled path on long rows, one-batch form: 16 wavefronts, four per
+                                     // SIMD, which is what keeps the slot loop's LDS round trips and arithmetic hidden
+constexpr int kTileThreads = 512;    // the same for shapes the one-batch form does not take (more than 64 learners at
+                                     // 16 B per lane): 8 wavefronts with up to 256 registers, several batches per tile
 constexpr int kUnroll = 8;           // rows whose loads are in flight together per lane
 using plan::kMaxGrid;                // upper bound on persistent workgroups (partials buffer sizing)
 constexpr int kGridPerCu = 4;        // persistent workgroups per compute unit (16 waves per CU)
@@ -304,6 +306,11 @@ __device__ __forceinline__ void pivot_of(f32x4 x, double* s) {
 #pragma unroll
     for (int k = 0; k < 4; ++k) s[k] = (double)x[k];
 }
+__device__ __forceinline__ void floats_of(float x, float* f) { f[0] = x; }
+__device__ __forceinline__ void floats_of(f32x4 x, float* f) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) f[k] = x[k];
+}
 
 // Running sums of one lane's column group; the first value it is given becomes the pivot (kept as
 // the fp32 value it is).  The squares of all the group's columns share one accumulator: only their
@@ -438,12 +445,22 @@ __device__ __forceinline__ void ring_walk(const float* xc, float* oc, const GT* 
 // by lane and only the plain sums need merging per column: across the row groups that share a wavefront by
 // shuffles, across wavefronts through one LDS slot each, summed in fixed order.
 // ---------------------------------------------------------------------------------------
+// The value of the lane whose number differs in bit 0 (CTRL 0xB1: quad order 1,0,3,2) or bit 1 (0x4E: 2,3,0,1),
+// moved inside the vector unit (no LDS round trip).  All four lanes of a quad must be active.
+template <int CTRL>
+__device__ __forceinline__ double lane_xor_quad(double v) {
+    const long long bits = __double_as_longlong(v);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(bits & 0xFFFFFFFFll), CTRL, 0xF, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(bits >> 32), CTRL, 0xF, 0xF, false);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+
 // The large workgroup is alone on its compute unit and may use 256 registers per lane: 8 rows in flight (8
 // wavefronts x 8 rows cover n = 64 at once).  The small one, which serves short rows (launches bound by latency,
 // several workgroups per CU) and shares the 3-slot kernel with the ring walk there, stays frugal.
 template <int T> struct TileShape {
-    static constexpr int RB = T > 256 ? 8 : 2;   // rows per lane and batch
-    static constexpr int SB = T > 256 ? 3 : 2;   // rows whose slot chains advance together (two slots per trip each);
+    static constexpr int RB = T > 512 ? 4 : T > 256 ? 8 : 2;   // rows per lane and batch
+    static constexpr int SB = T == 512 ? 3 : 2;   // rows whose slot chains advance together (two slots per trip each);
                                                  // more rows at once cost registers and ran slower (4: -1 to -6 %)
 };
 
@@ -461,10 +478,14 @@ struct TileCtx {
 template <int VEC>
 struct TileStats {
     double piv[VEC], a[VEC], sq;
+    float pivf[VEC];   // the pivot as the fp32 output it is (row groups with a pivot of their own keep it in this form)
     __device__ __forceinline__ void reset() {
         sq = 0.0;
 #pragma unroll
-        for (int k = 0; k < VEC; ++k) piv[k] = a[k] = 0.0;
+        for (int k = 0; k < VEC; ++k) {
+            piv[k] = a[k] = 0.0;
+            pivf[k] = 0.0f;
+        }
     }
 };
 
@@ -483,15 +504,17 @@ struct TileStats {
 // OWNPIV (with CLAMP and CD): no extra item; the lane's first own output is its pivot, and the merge at the end
 // of the tile brings the row groups' sums to one common pivot (tile_finish_own).
 //
-// `feed(j0)` runs in front of every group of SB rows: the caller's place for the loads of a later tile, so that
-// they enter the memory pipeline a few at a time between the rows' arithmetic instead of in one burst.
+// `feed(j0)` runs in front of every group of SB rows and `refill(j0)` behind it (its gradients have been used,
+// its outputs stored): the caller's places for the loads of the next tiles, so that they enter the memory
+// pipeline a few at a time between the rows' arithmetic instead of in one burst.
 struct NoFeed {
     __device__ __forceinline__ void operator()(int) const {}
 };
-template <int VEC, bool CD, int RB, int SB, bool CLAMP, bool OWNPIV, typename GR, typename FEED = NoFeed>
+template <int VEC, bool CD, int RB, int SB, bool CLAMP, bool OWNPIV, typename GR, typename FEED = NoFeed,
+          typename REFILL = NoFeed>
 __device__ __forceinline__ void tile_rows(const TileCtx<VEC>& c, const typename Cols<VEC>::T* cur, int b, const GR (&g)[RB],
                                           GR g0, bool with_pivot, bool active, float* out_col, int64_t ldo,
-                                          TileStats<VEC>& st, const FEED& feed = FEED{}) {
+                                          TileStats<VEC>& st, const FEED& feed = FEED{}, const REFILL& refill = REFILL{}) {
     typedef typename Cols<VEC>::T V;
     constexpr int P = (CD && !OWNPIV) ? 1 : 0, ITEMS = RB + P;
 #pragma unroll
@@ -521,8 +544,9 @@ __device__ __forceinline__ void tile_rows(const TileCtx<VEC>& c, const typename 
 #pragma unroll
             for (int i = 0; i < SB; ++i) acc[i] = cur[e[i].off + c.tlane] * e[i].w;
         }
-        int s = 1;
-        for (; s + 1 < c.deg; s += 2) {
+        // two slots per trip; where four wavefronts share a SIMD they hide each other's round trips and the
+        // registers are worth more than a longer unrolled trip
+        auto trip = [&](int s) {
             TileSlot e0[SB], e1[SB];
             V x0[SB], x1[SB];
 #pragma unroll
@@ -540,6 +564,13 @@ __device__ __forceinline__ void tile_rows(const TileCtx<VEC>& c, const typename 
                 acc[i] = vfma(e0[i].w, x0[i], acc[i]);
                 acc[i] = vfma(e1[i].w, x1[i], acc[i]);
             }
+        };
+        int s = 1;
+        if (RB == 4) {
+#pragma unroll 1
+            for (; s + 1 < c.deg; s += 2) trip(s);
+        } else {
+            for (; s + 1 < c.deg; s += 2) trip(s);
         }
         if (s < c.deg) {
             TileSlot e[SB];
@@ -557,13 +588,13 @@ __device__ __forceinline__ void tile_rows(const TileCtx<VEC>& c, const typename 
                 if (CLAMP || ok[i]) {
                     const V out = vfma(c.neg_lr, widen_g(g[j - P < 0 ? 0 : j - P]), acc[i]);
                     st_x(out_col + (int64_t)row[i] * ldo, out);
-                    if (CD && OWNPIV && j == 0) pivot_of(out, st.piv);
+                    if (CD && OWNPIV && j == 0) floats_of(out, st.pivf);
                     if (CD && ok[i]) {
                         double o[VEC];
                         pivot_of(out, o);      // widen
 #pragma unroll
                         for (int k = 0; k < VEC; ++k) {
-                            const double df = o[k] - st.piv[k];
+                            const double df = o[k] - (OWNPIV ? (double)st.pivf[k] : st.piv[k]);
                             st.a[k] += df;
                             st.sq = fma(df, df, st.sq);
                         }
@@ -571,6 +602,7 @@ __device__ __forceinline__ void tile_rows(const TileCtx<VEC>& c, const typename 
                 }
             }
         }
+        refill(j0);
     }
 }
 
@@ -624,26 +656,57 @@ __device__ __forceinline__ void tile_finish_own(const TileCtx<VEC>& c, double* c
 #pragma unroll
     for (int k = 0; k < VEC; ++k) {
         comb[mine + k] = st.a[k];
-        combp[mine + k] = (float)st.piv[k];      // the pivot is an fp32 output: nothing is lost
+        combp[mine + k] = st.pivf[k];
     }
     total += st.sq;
     lds_barrier();
-    // one lane per column (the tile has lpr * VEC of them, spread over the whole workgroup: a merge left to one
-    // wavefront would keep all the others waiting at the barrier below)
-    for (int idx = threadIdx.x; idx < live_cols * VEC; idx += T) {
-        const double p0 = (double)combp[idx];    // row group 0 owns row 0: its pivot is the common one
-        double at = 0.0, corr = 0.0;
-        for (int q = 0; q < c.nrg; ++q) {
-            const int m = c.rows_each + (q < c.rows_more ? 1 : 0);     // rows q, q + nrg, ... below n
-            if (m) {
-                const double md = (double)m;
-                const size_t at_q = (size_t)q * c.lpr * VEC + idx;
-                const double aq = comb[at_q], dq = (double)combp[at_q] - p0;
-                at += fma(md, dq, aq);
-                corr += dq * fma(md, dq, 2.0 * aq);
-            }
+    // The tile has lpr * VEC columns and nrg partial sums per column.  Where there are more lanes than columns
+    // (1 KB row segments: four times as many) `parts` adjacent lanes share a column, each takes nrg / parts of its
+    // row groups and a symmetric exchange adds the shares up, the same bits in every lane of the column.  (Left
+    // to one lane per column the loop over the row groups is a chain of LDS round trips on a quarter of the
+    // wavefronts while the others wait at the barrier below.)
+    // Nothing here branches on data: every lane reads VEC slots (clamped to slot 0 where it has fewer), all
+    // reads are issued before the first is used, and a slot that does not count enters with weight 0.
+    const int parts = c.nrg >= VEC ? c.nrg / VEC : 1;        // a power of two; the lanes of a column sit side by side in one wavefront
+    const int each = c.nrg / parts;                          // row groups per lane: min(nrg, VEC)
+    const int cols = c.lpr * VEC;
+    for (int idx = threadIdx.x; idx < live_cols * VEC * parts; idx += T) {
+        const int col = idx / parts, part = idx % parts;
+        double aq[VEC], md[VEC];
+        float pq[VEC];
+        const float p0f = combp[col];                        // row group 0 owns row 0: its pivot is the common one
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            const bool on = k < each;                        // uniform
+            const int q = on ? part * each + k : 0;
+            const size_t at_q = (size_t)q * cols + col;
+            aq[k] = comb[at_q];
+            pq[k] = combp[at_q];
+            md[k] = on ? (double)(c.rows_each + (q < c.rows_more ? 1 : 0)) : -1.0;   // rows q, q + nrg, ... below n
         }
-        total += corr - at * at * inv_n;
+        const double p0 = (double)p0f;
+        double at = 0.0, corr = 0.0;
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            const double dq = (double)pq[k] - p0;
+            const double tq = fma(md[k], dq, aq[k]);         // a row group without rows has a = 0 and weight 0: no share
+            const double cq = dq * (tq + aq[k]);
+            at += md[k] >= 0.0 ? tq : 0.0;
+            corr += md[k] >= 0.0 ? cq : 0.0;
+        }
+        if (parts > 1) {
+            at += lane_xor_quad<0xB1>(at);                   // lanes 1 apart
+            corr += lane_xor_quad<0xB1>(corr);
+        }
+        if (parts > 2) {
+            at += lane_xor_quad<0x4E>(at);                   // lanes 2 apart
+            corr += lane_xor_quad<0x4E>(corr);
+        }
+        for (int off = 4; off < parts; off <<= 1) {
+            at += __shfl_xor(at, off, 64);
+            corr += __shfl_xor(corr, off, 64);
+        }
+        if (part == 0) total += corr - at * at * inv_n;
     }
     lds_barrier();                                     // the merge slots are free again
 }
@@ -719,96 +782,6 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
         stash(rg, t, b, cur, xs);
     }
 
-    if (T > 256 && nb == 1 && lpr >= 64) {
-        // A tile is one batch of whole-wavefront rows (n <= 64 with 1 KB row segments, fewer learners with wider
-        // ones): X runs TWO tiles ahead in registers and the gradients one, so that a load has a whole tile's time
-        // to arrive before its value is needed and about two tiles of X are in flight per compute unit at any
-        // time.  The two register sets swap roles every tile (the loop is unrolled by two so that no register is
-        // copied: a copy would wait for a load issued a moment ago).  Every load and store in this loop is
-        // unconditional (see tile_rows): rows, columns and tiles beyond the end are clamped to the last valid one.
-        const int q = __builtin_amdgcn_readfirstlane(rg);      // a row group is whole wavefronts: its number is a scalar
-        c.rg = q;
-        const int last_row = n - 1;
-        auto cge_of = [&](int64_t tile) {                       // the lane's column group in `tile`, clamped
-            const int64_t cg = tile * lpr + lane;
-            return cg < ncg ? cg : ncg - 1;
-        };
-        auto ld_xs = [&](int64_t tile, V (&xs)[RB]) {
-            const int64_t col = cge_of(tile) * VEC;
-#pragma unroll
-            for (int u = 0; u < RB; ++u) {
-                int r = q + u * nrg;
-                r = r < last_row ? r : last_row;
-                xs[u] = ld_x(X + (int64_t)r * ld.x + col, tag);
-            }
-        };
-        auto ld_gs = [&](int64_t tile, GR (&g)[RB]) {
-            const int64_t col = cge_of(tile) * VEC;
-#pragma unroll
-            for (int u = 0; u < RB; ++u) {
-                int r = q + u * nrg;
-                r = r < last_row ? r : last_row;
-                g[u] = ld_g_raw(G + (int64_t)r * ld.g + col, tag);
-            }
-        };
-        float* combp = reinterpret_cast<float*>(comb + (size_t)nrg * lpr * VEC);   // pivots, behind the sums
-        V xa[RB], xb[RB];
-        GR ga[RB], gb[RB];
-        ld_xs(t + step, xa);
-        ld_gs(t, ga);
-        lds_barrier();
-        // one tile: issue X of tile t + 2 step into `xi` and gradients of t + step into `gi`, compute tile t with
-        // `gu`, stage X of tile t + step (issued one tile ago into `xw`) into the other buffer
-#define PSGD_TILE_ROUND(xw, xi, gu, gi)                                                                                  \
-    do {                                                                                                                 \
-        const int64_t colx = cge_of(t + 2 * step) * VEC, colg = cge_of(t + step) * VEC;                                  \
-        auto feed = [&](int j0) {                                                                                        \
-            __builtin_amdgcn_sched_barrier(0);                                                                           \
-            _Pragma("unroll") for (int i = 0; i < SB; ++i) {                                                             \
-                const int u = j0 + i;                                                                                    \
-                if (u < RB) {                                                                                            \
-                    int r = q + u * nrg;                                                                                 \
-                    r = r < last_row ? r : last_row;                                                                     \
-                    xi[u] = ld_x(X + (int64_t)r * ld.x + colx, tag);                                                     \
-                    gi[u] = ld_g_raw(G + (int64_t)r * ld.g + colg, tag);                                                 \
-                }                                                                                                        \
-            }                                                                                                            \
-            __builtin_amdgcn_sched_barrier(0);                                                                           \
-        };                                                                                                               \
-        const int64_t cge = cge_of(t);                                                                                   \
-        const bool active = t * lpr + lane < ncg;                                                                        \
-        c.tlane = (int)(cge - t * lpr);                                                                                  \
-        if (CD) st.reset();                                                                                              \
-        tile_rows<VEC, CD, RB, SB, true, true>(c, cur, 0, gu, GR{}, false, active, Xout + cge * VEC, ld.o, st, feed);    \
-        {                                                                                                                \
-            const int lane_n = (int)(cge_of(t + step) - (t + step) * lpr);   /* negative beyond the last tile */          \
-            _Pragma("unroll") for (int u = 0; u < RB; ++u) {                                                             \
-                int r = q + u * nrg;                                                                                     \
-                r = r < last_row ? r : last_row;                                                                         \
-                if (lane_n >= 0) nxt[r * lpr + lane_n] = xw[u];                                                          \
-            }                                                                                                            \
-        }                                                                                                                \
-        if (CD) {                                                                                                        \
-            const int64_t left = ncg - t * lpr;                       /* column groups of this tile (uniform) */         \
-            tile_finish_own<VEC, T>(c, comb, combp, (int)(left < lpr ? left : lpr), st, inv_n, total);                   \
-        } else {                                                                                                         \
-            lds_barrier();                                                                                               \
-        }                                                                                                                \
-        V* sw_ = cur;                                                                                                    \
-        cur = nxt;                                                                                                       \
-        nxt = sw_;                                                                                                       \
-        t += step;                                                                                                       \
-    } while (0)
-        for (;;) {
-            PSGD_TILE_ROUND(xa, xb, ga, gb);
-            if (t >= ntiles) break;
-            PSGD_TILE_ROUND(xb, xa, gb, ga);
-            if (t >= ntiles) break;
-        }
-#undef PSGD_TILE_ROUND
-        return total;
-    }
-
     // Several batches per tile: batch b of the next tile travels while batch b of this one is computed, the
     // gradients one batch ahead.
     GR gcur[RB], g0 = {};
@@ -842,6 +815,130 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
         cur = nxt;
         nxt = sw;
         t = tn;
+    }
+    return total;
+}
+
+// The tiled path of the large workgroup (1024 lanes, alone on its compute unit) for tables whose tile is ONE
+// batch of whole-wavefront rows: lpr >= 64 and at most TileShape<T>::RB rows per lane (n <= 64 with 1 KB row
+// segments, fewer learners with wider ones).  The launcher picks the shape (plan::tile_plan, one-batch form).
+// With `comb_in_tile` the merge slots of the distance are the tile buffer that has just been consumed.
+template <int VEC, typename GT, bool CD, int T>
+__device__ double tile_path_deep(const float* X, float* Xout, const GT* __restrict__ G, const TileSlot* tab, char* tiles,
+                                 int n, int deg, Pitch ld, int64_t ncg, float neg_lr, int lpr, double inv_n,
+                                 bool comb_in_tile) {
+    typedef typename Cols<VEC>::T V;
+    typedef typename RawG<GT, VEC>::T GR;
+    const Cols<VEC> tag{};
+    constexpr int RB = TileShape<T>::RB, SB = TileShape<T>::SB;
+    TileCtx<VEC> c;
+    c.tab = tab;
+    c.n = n;
+    c.deg = deg;
+    c.lpr = lpr;
+    c.lane = c.tlane = threadIdx.x % lpr;
+    c.nrg = T / lpr;
+    c.rows_each = n / c.nrg;
+    c.rows_more = n % c.nrg;
+    c.neg_lr = neg_lr;
+    const int lane = c.lane, nrg = c.nrg;
+    const size_t tile_bytes = (((size_t)n * lpr * sizeof(V)) + 15) & ~(size_t)15;
+    V* cur = reinterpret_cast<V*>(tiles);
+    V* nxt = reinterpret_cast<V*>(tiles + tile_bytes);
+    double* comb = reinterpret_cast<double*>(tiles + 2 * tile_bytes);   // [nrg][lpr][VEC] sums, then as many float pivots
+    const int64_t ntiles = (ncg + lpr - 1) / lpr;
+    const int64_t step = gridDim.x;
+    int64_t t = plan::die_contiguous_slot(blockIdx.x, gridDim.x, kXcds);   // the first of tiles t, t + step, ...
+    if (t >= ntiles) return 0.0;                             // uniform: the whole workgroup has nothing to do
+    double total = 0.0;
+    TileStats<VEC> st;
+    // A tile is one batch of whole-wavefront rows (n <= 64 with 1 KB row segments, fewer learners with wider
+    // ones).  A lane keeps ONE register per row for X and one for the gradients, each reloaded the moment
+    // its value has been used, so every load has a whole tile's time to arrive:
+    //   in front of a group of rows: X of tile t + step (loaded one tile ago) goes into the other LDS buffer,
+    //       which nobody reads during this tile, and the same registers are loaded with tile t + 2 step;
+    //   behind it: its gradients (tile t) have been used, the registers are loaded with tile t + step.
+    // The loads thus enter the memory pipeline a few at a time between the arithmetic.  (Issued in one burst
+    // at the start of the tile they hold the wavefront at the issue stage until the pipeline has taken them,
+    // and the arithmetic starts only then: the two times add up instead of overlapping.)  Every load and
+    // store here is unconditional (see tile_rows): rows, columns and tiles beyond the end are clamped to the
+    // last valid one.
+    const int q = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / lpr));   // a row group is whole wavefronts: its number is a scalar
+    c.rg = q;
+    const int last_row = n - 1;
+    auto cge_of = [&](int64_t tile) {                       // the lane's column group in `tile`, clamped
+        const int64_t cg = tile * lpr + lane;
+        return cg < ncg ? cg : ncg - 1;
+    };
+    auto row_of = [&](int u) {
+        const int r = q + u * nrg;
+        return r < last_row ? r : last_row;
+    };
+    V x[RB];
+    GR g[RB];
+    if (t * lpr + lane < ncg) {                              // the first tile: straight into `cur`
+#pragma unroll
+        for (int u = 0; u < RB; ++u) {
+            const int r = q + u * nrg;
+            if (r < n) cur[r * lpr + lane] = ld_x(X + (int64_t)r * ld.x + (t * lpr + lane) * VEC, tag);
+        }
+    }
+    {
+        const int64_t colx = cge_of(t + step) * VEC, colg = cge_of(t) * VEC;
+#pragma unroll
+        for (int u = 0; u < RB; ++u) {
+            x[u] = ld_x(X + (int64_t)row_of(u) * ld.x + colx, tag);
+            g[u] = ld_g_raw(G + (int64_t)row_of(u) * ld.g + colg, tag);
+        }
+    }
+    lds_barrier();
+    for (;;) {
+        const int64_t colx = cge_of(t + 2 * step) * VEC, colg = cge_of(t + step) * VEC;
+        const int lane_n = (int)(cge_of(t + step) - (t + step) * lpr);   // negative beyond the last tile
+        auto feed = [&](int j0) {
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < SB; ++i) {
+                const int u = j0 + i;
+                if (u < RB) {
+                    const int r = row_of(u);
+                    if (lane_n >= 0) nxt[r * lpr + lane_n] = x[u];
+                    x[u] = ld_x(X + (int64_t)r * ld.x + colx, tag);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        auto refill = [&](int j0) {
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < SB; ++i) {
+                const int u = j0 + i;
+                if (u < RB) g[u] = ld_g_raw(G + (int64_t)row_of(u) * ld.g + colg, tag);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        const int64_t cge = cge_of(t);
+        const bool active = t * lpr + lane < ncg;
+        c.tlane = (int)(cge - t * lpr);
+        if (CD) st.reset();
+        tile_rows<VEC, CD, RB, SB, true, true>(c, cur, 0, g, GR{}, false, active, Xout + cge * VEC, ld.o, st, feed, refill);
+        if (CD) {
+            const int64_t left = ncg - t * lpr;                       // column groups of this tile (uniform)
+            double* sums = comb;
+            if (comb_in_tile) {                                       // uniform
+                lds_barrier();                                        // every row of `cur` has been read
+                sums = reinterpret_cast<double*>(cur);
+            }
+            tile_finish_own<VEC, T>(c, sums, reinterpret_cast<float*>(sums + (size_t)nrg * lpr * VEC),
+                                    (int)(left < lpr ? left : lpr), st, inv_n, total);
+        } else {
+            lds_barrier();
+        }
+        V* sw = cur;
+        cur = nxt;
+        nxt = sw;
+        t += step;
+        if (t >= ntiles) break;
     }
     return total;
 }
@@ -918,11 +1015,13 @@ __global__ __launch_bounds__(T, 3) void mix_step_kernel(const float* X, float* X
 // skip_rings (3-slot tables only): the launcher enqueues this kernel behind the ring-walk kernel because only
 // the device can tell which of the two a table needs; both classify it with the same code, and the one it does
 // not belong to writes nothing (and contributes 0 to the distance).
-template <int VEC, typename GT, bool CD, int T>
+//
+// DEEP: the large workgroup's one-batch form (tile_path_deep); the launcher has planned lpr for it.
+template <int VEC, typename GT, bool CD, int T, bool DEEP>
 __global__ __launch_bounds__(T) void mix_deg_kernel(const float* X, float* Xout, const GT* __restrict__ G,
                                                     const int32_t* __restrict__ nbr, const float* __restrict__ w,
                                                     int deg, int n, int64_t d, Pitch ld, float neg_lr, int lpr,
-                                                    int skip_rings, double* __restrict__ partials) {
+                                                    int skip_rings, int comb_in_tile, double* __restrict__ partials) {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     __shared__ double lds_waves[T / 64];
     const size_t tab_bytes = (((size_t)n * deg * sizeof(TileSlot)) + 15) & ~(size_t)15;
@@ -947,8 +1046,13 @@ __global__ __launch_bounds__(T) void mix_deg_kernel(const float* X, float* Xout,
         if (CD && threadIdx.x == 0) partials[blockIdx.x] = __builtin_nan("");
         return;
     }
-    const double total = tile_path<VEC, GT, CD, T>(X, Xout, G, tab, lds_raw + tab_bytes, n, deg, ld, d / VEC, neg_lr, lpr,
-                                                   1.0 / (double)n);
+    double total;
+    if (DEEP)
+        total = tile_path_deep<VEC, GT, CD, T>(X, Xout, G, tab, lds_raw + tab_bytes, n, deg, ld, d / VEC, neg_lr, lpr,
+                                               1.0 / (double)n, comb_in_tile != 0);
+    else
+        total = tile_path<VEC, GT, CD, T>(X, Xout, G, tab, lds_raw + tab_bytes, n, deg, ld, d / VEC, neg_lr, lpr,
+                                          1.0 / (double)n);
     if (CD) {
         const double bs = block_sum<T>(total, lds_waves);
         if (threadIdx.x == 0) partials[blockIdx.x] = bs;
@@ -1596,11 +1700,22 @@ int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
     if (deg != 3 || big) {
         // Tiled kernel: every table with another slot count, and behind the ring walk for 3-slot tables, where
         // it does the work only if the table turns out not to be one ring (decided on the device by both).
-        const int wg_threads = big ? kTileThreads : kThreads;
+        // Long rows: the 1024-lane one-batch form where the shape allows it (n <= 64 at 1 KB row segments), else
+        // 512 lanes with several batches per tile.  Short rows: small workgroups, several per compute unit.
         const size_t base = 0;
-        const int rpb = big ? TileShape<kTileThreads>::RB : TileShape<kThreads>::RB;
-        plan::TilePlan tp = plan::tile_plan(n, deg, vec, wg_threads, want_cd, big ? kLdsCapLarge : kLdsCapSmall, base, rpb);
-        if (tp.lpr == 0 && !big) tp = plan::tile_plan(n, deg, vec, wg_threads, want_cd, kLdsCapLarge, base, rpb);
+        plan::TilePlan tp;
+        tp.lpr = 0;
+        bool deep = false;
+        const int deep_threads = want_cd ? kTileThreads : kDeepThreads;
+        if (big) {
+            tp = plan::tile_plan(n, deg, vec, deep_threads, want_cd, kLdsCapLarge, base,
+                                 want_cd ? TileShape<kTileThreads>::RB : TileShape<kDeepThreads>::RB, true);
+            deep = tp.lpr != 0;
+            if (!deep) tp = plan::tile_plan(n, deg, vec, kTileThreads, want_cd, kLdsCapLarge, base, TileShape<kTileThreads>::RB);
+        } else {
+            tp = plan::tile_plan(n, deg, vec, kThreads, want_cd, kLdsCapSmall, base, TileShape<kThreads>::RB);
+            if (tp.lpr == 0) tp = plan::tile_plan(n, deg, vec, kThreads, want_cd, kLdsCapLarge, base, TileShape<kThreads>::RB);
+        }
         if (tp.lpr == 0)
             return fail(PSGD_EINVAL, "%s: n=%d, deg=%d does not fit the tiled path's LDS", name, n, deg);
         const int lpr = tp.lpr;
@@ -1609,9 +1724,9 @@ int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
         const int64_t ntiles = (d / vec + lpr - 1) / lpr;
         const int first = grid;
         int tgrid = 0;
-#define PSGD_DEG_LAUNCH(VEC, CD, T)                                                                                     \
+#define PSGD_DEG_LAUNCH(VEC, CD, T, DEEP)                                                                                   \
     do {                                                                                                                \
-        const void* fn = reinterpret_cast<const void*>(mix_deg_kernel<VEC, GT, CD, T>);                                 \
+        const void* fn = reinterpret_cast<const void*>(mix_deg_kernel<VEC, GT, CD, T, DEEP>);                           \
         if (int rc = allow_lds(fn, lds_bytes)) return rc;                                                               \
         int per_cu = resident_per_cu(fn, lds_bytes, T);                                                                 \
         if (per_cu > 2 * kGridPerCu) per_cu = 2 * kGridPerCu;                                                           \
@@ -1623,13 +1738,16 @@ int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
                 break;                                                                                                  \
             }                                                                                                           \
         }                                                                                                               \
-        hipLaunchKernelGGL((mix_deg_kernel<VEC, GT, CD, T>), dim3(tgrid), dim3(T), lds_bytes, s, X, X_out, G, nbr, w,   \
-                           deg, n, d, ld, neg_lr, lpr, deg == 3 ? 1 : 0, CD ? partials + first : partials);             \
+        hipLaunchKernelGGL((mix_deg_kernel<VEC, GT, CD, T, DEEP>), dim3(tgrid), dim3(T), lds_bytes, s, X, X_out, G,     \
+                           nbr, w,                                                                                     \
+                           deg, n, d, ld, neg_lr, lpr, deg == 3 ? 1 : 0, tp.comb_in_tile ? 1 : 0,                    \
+                           CD ? partials + first : partials);             \
     } while (0)
 #define PSGD_DEG_PICK(VEC, CD)                                                                                          \
     do {                                                                                                                \
-        if (big) PSGD_DEG_LAUNCH(VEC, CD, kTileThreads);                                                                \
-        else PSGD_DEG_LAUNCH(VEC, CD, kThreads);                                                                        \
+        if (deep) PSGD_DEG_LAUNCH(VEC, CD, (CD ? kTileThreads : kDeepThreads), true);                                   \
+        else if (big) PSGD_DEG_LAUNCH(VEC, CD, kTileThreads, false);                                                    \
+        else PSGD_DEG_LAUNCH(VEC, CD, kThreads, false);                                                                 \
     } while (0)
         if (vec4 && want_cd) PSGD_DEG_PICK(4, true);
         else if (vec4) PSGD_DEG_PICK(4, false);

@@ -911,13 +911,16 @@ def _two_rings_table(n):
     return nbr, np.tile(np.asarray([0.5, 0.25, 0.25], dtype=np.float32), (n, 1))
 
 
-@pytest.mark.parametrize("n,d", [(64, 1_600_004), (64, 1_572_867), (128, 1_600_004), (33, 1_700_004), (8, 1_800_004)])
+@pytest.mark.parametrize("n,d", [(64, 1_600_004), (64, 1_572_867), (128, 1_600_004), (33, 1_700_004), (8, 1_800_004),
+                                 (70, 1_600_004), (16, 1_900_004), (5, 2_000_004), (48, 1_600_003)])
 @pytest.mark.parametrize("kind", ["two_rings", "deg5", "deg13"])
 @pytest.mark.parametrize("gkind", ["f32", "bf16"])
 def test_tiled_kernel_long_rows_every_element(psgd, n, d, kind, gkind):
-    """Rows long enough for the large-workgroup tiled kernel (tiles two ahead in registers for n <= 64, one
-    ahead for n = 128, wide rows for n = 8; d not a multiple of 4 takes one column per lane): every element
-    and the fused distance against the oracle, out of place and in place, ragged last tile included."""
+    """Rows long enough for the large-workgroup tiled kernels: the 1024-lane one-batch form for n <= 64 (merge
+    slots of the distance inside the consumed tile buffer at 16 B per lane; wider rows for n = 16, 8, 5; an odd
+    row count per row group for n = 33, 48), the 512-lane form with several batches per tile for n = 70 and
+    n = 128; d not a multiple of 4 takes one column per lane.  Every element and the fused distance against
+    the oracle, out of place and in place, ragged last tile included."""
     rng = np.random.default_rng(n + d % 1000)
     if kind == "two_rings":
         if n % 2:
