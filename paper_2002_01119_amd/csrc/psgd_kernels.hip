@@ -566,7 +566,7 @@ __device__ __forceinline__ void tile_rows(const TileCtx<VEC>& c, const typename 
             }
         };
         int s = 1;
-        if (RB == 4) {
+        if (RB == 4 || (CLAMP && CD && sizeof(GR) > 8)) {
 #pragma unroll 1
             for (; s + 1 < c.deg; s += 2) trip(s);
         } else {
@@ -892,9 +892,15 @@ __device__ double tile_path_deep(const float* X, float* Xout, const GT* __restri
         }
     }
     lds_barrier();
-    for (;;) {
+    // One tile.  It runs once in front of the loop and then inside it: the waits for the loads of the tile before
+    // are counted per place in the program, and a place that both the start and the loop reach waits for the
+    // smaller count, the start's, where fewer operations have been issued since.
+    auto one_tile = [&]() __attribute__((always_inline)) {
         const int64_t colx = cge_of(t + 2 * step) * VEC, colg = cge_of(t + step) * VEC;
-        const int lane_n = (int)(cge_of(t + step) - (t + step) * lpr);   // negative beyond the last tile
+        // where tile t + step goes in the other buffer: the lane's own slot, the last valid lane's at the ragged
+        // end (the same value twice), and beyond the last tile anywhere (nobody will read it) - never a branch
+        const int lane_to = (int)(cge_of(t + step) - (t + step) * lpr);
+        const int lane_n = lane_to >= 0 ? lane_to : lane;
         auto feed = [&](int j0) {
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -902,7 +908,7 @@ __device__ double tile_path_deep(const float* X, float* Xout, const GT* __restri
                 const int u = j0 + i;
                 if (u < RB) {
                     const int r = row_of(u);
-                    if (lane_n >= 0) nxt[r * lpr + lane_n] = x[u];
+                    nxt[r * lpr + lane_n] = x[u];
                     x[u] = ld_x(X + (int64_t)r * ld.x + colx, tag);
                 }
             }
@@ -938,8 +944,9 @@ __device__ double tile_path_deep(const float* X, float* Xout, const GT* __restri
         cur = nxt;
         nxt = sw;
         t += step;
-        if (t >= ntiles) break;
-    }
+    };
+    one_tile();
+    while (t < ntiles) one_tile();
     return total;
 }
 
