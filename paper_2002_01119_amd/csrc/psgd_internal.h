@@ -82,26 +82,29 @@ inline SweepPlan sweep_plan(int64_t ncg, int grid, int threads) {
 // bytes the kernel keeps for itself, fits `cap`; rows wider than a wavefront (lpr > 64) are only taken while a
 // lane still gets at most `rows_per_batch` rows, which is what few learners need to keep enough bytes in flight
 // (n = 16: 256 lanes per row, 8 rows per lane).  lpr = 0 if not even one lane per row fits.
+constexpr int kOneBatchMinLpr = 16;
 struct TilePlan {
     int lpr;
     bool comb_in_tile;   // one-batch form only: the merge slots of the distance live in the tile buffer just consumed
     size_t tab_bytes, tile_bytes, comb_bytes, total;
 };
-// one_batch: plan for the large workgroup's one-batch form, which needs whole-wavefront rows (lpr >= 64) and every
-// row of a tile in one batch (at most rows_per_batch rows per lane); it may put the merge slots into the buffer it
-// has finished reading (one more barrier per tile) when they do not fit beside the two tiles.
+// one_batch: plan for the large workgroup's one-batch form, which needs every row of a tile in one batch (at most
+// rows_per_batch rows per lane) and at least 16 lanes per row (256-byte row segments at 16 B per lane; also what
+// keeps the lanes that share a column in the merge of the distance inside one wavefront); it may put the merge
+// slots into the buffer it has finished reading (one more barrier per tile) when they do not fit beside the two
+// tiles.
 inline TilePlan tile_plan(int n, int deg, int vec, int threads, bool cd, size_t cap, size_t base, int rows_per_batch,
                           bool one_batch = false) {
     TilePlan p;
     p.comb_in_tile = false;
     p.tab_bytes = (((size_t)n * deg * 8) + 15) & ~(size_t)15;
-    for (p.lpr = threads; p.lpr >= (one_batch ? 64 : 1); p.lpr >>= 1) {
+    for (p.lpr = threads; p.lpr >= (one_batch ? kOneBatchMinLpr : 1); p.lpr >>= 1) {
         const int nrg = threads / p.lpr;
         const int rows = (n + nrg - 1) / nrg;
         if ((one_batch || p.lpr > 64) && rows > rows_per_batch) continue;
-        const int slots = p.lpr <= 64 ? threads / 64 : nrg;
+        const int slots = (one_batch || p.lpr > 64) ? nrg : threads / 64;   // one per row group, or per wavefront where row groups share one
         p.tile_bytes = (((size_t)n * p.lpr * vec * 4) + 15) & ~(size_t)15;
-        p.comb_bytes = cd ? (size_t)slots * p.lpr * vec * (p.lpr >= 64 ? 12 : 8) : 0;   // + a float pivot per slot for whole-wavefront rows
+        p.comb_bytes = cd ? (size_t)slots * p.lpr * vec * (one_batch ? 12 : 8) : 0;   // one-batch form: + a float per slot, the row group's own pivot
         p.total = base + p.tab_bytes + 2 * p.tile_bytes + p.comb_bytes;
         if (p.total <= cap) return p;
         if (one_batch && cd && p.comb_bytes <= p.tile_bytes && p.total - p.comb_bytes <= cap) {

@@ -647,8 +647,8 @@ __device__ __forceinline__ void tile_finish(const TileCtx<VEC>& c, double* comb,
 //     sum_i (o_i - P)   = sum_q (a_q + m_q D_q)
 //     sum_i (o_i - P)^2 = sum_q (sq_q + 2 D_q a_q + m_q D_q^2)
 // exactly; in fp64 the corrections are of the size of the sums themselves (every pivot is one of the outputs).
-// If all outputs of a column are equal every D_q is 0 and the distance comes out exactly 0.  Row groups are whole
-// wavefronts here (lpr >= 64): one slot per row group, a double for the sum and a float for the pivot.
+// If all outputs of a column are equal every D_q is 0 and the distance comes out exactly 0.  One slot per row
+// group and column: a double for the sum and a float for the pivot.
 template <int VEC, int T>
 __device__ __forceinline__ void tile_finish_own(const TileCtx<VEC>& c, double* comb, float* combp, int live_cols,
                                                 TileStats<VEC>& st, double inv_n, double& total) {
@@ -819,11 +819,16 @@ __device__ double tile_path(const float* X, float* Xout, const GT* __restrict__ 
     return total;
 }
 
-// The tiled path of the large workgroup (1024 lanes, alone on its compute unit) for tables whose tile is ONE
-// batch of whole-wavefront rows: lpr >= 64 and at most TileShape<T>::RB rows per lane (n <= 64 with 1 KB row
-// segments, fewer learners with wider ones).  The launcher picks the shape (plan::tile_plan, one-batch form).
+// The tiled path of the large workgroup (1024 lanes without the distance, 512 with it; alone on its compute
+// unit) for tables whose tile is ONE batch of rows: at most TileShape<T>::RB rows per lane (n = 64 with 1 KB row
+// segments, fewer learners with wider ones, up to 256 learners with narrower ones).  The launcher picks the
+// shape (plan::tile_plan, one-batch form).
 // With `comb_in_tile` the merge slots of the distance are the tile buffer that has just been consumed.
-template <int VEC, typename GT, bool CD, int T>
+//
+// UQ: a row group is whole wavefronts (lpr >= 64), so its number is the same in every lane of a wavefront and is
+// kept in a scalar register: row offsets and table addresses then cost no vector registers.  Narrower rows
+// (n > 64 at 16 B per lane: two or four row groups share a wavefront) keep it per lane.
+template <int VEC, typename GT, bool CD, int T, bool UQ>
 __device__ double tile_path_deep(const float* X, float* Xout, const GT* __restrict__ G, const TileSlot* tab, char* tiles,
                                  int n, int deg, Pitch ld, int64_t ncg, float neg_lr, int lpr, double inv_n,
                                  bool comb_in_tile) {
@@ -863,7 +868,7 @@ __device__ double tile_path_deep(const float* X, float* Xout, const GT* __restri
     // and the arithmetic starts only then: the two times add up instead of overlapping.)  Every load and
     // store here is unconditional (see tile_rows): rows, columns and tiles beyond the end are clamped to the
     // last valid one.
-    const int q = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / lpr));   // a row group is whole wavefronts: its number is a scalar
+    const int q = UQ ? __builtin_amdgcn_readfirstlane((int)(threadIdx.x / lpr)) : (int)(threadIdx.x / lpr);
     c.rg = q;
     const int last_row = n - 1;
     auto cge_of = [&](int64_t tile) {                       // the lane's column group in `tile`, clamped
@@ -1023,8 +1028,9 @@ __global__ __launch_bounds__(T, 3) void mix_step_kernel(const float* X, float* X
 // the device can tell which of the two a table needs; both classify it with the same code, and the one it does
 // not belong to writes nothing (and contributes 0 to the distance).
 //
-// DEEP: the large workgroup's one-batch form (tile_path_deep); the launcher has planned lpr for it.
-template <int VEC, typename GT, bool CD, int T, bool DEEP>
+// DEEP: 0 = several batches per tile (tile_path); 1, 2 = the large workgroup's one-batch form (tile_path_deep)
+// with whole-wavefront rows (1) or narrower ones (2); the launcher has planned lpr for it.
+template <int VEC, typename GT, bool CD, int T, int DEEP>
 __global__ __launch_bounds__(T) void mix_deg_kernel(const float* X, float* Xout, const GT* __restrict__ G,
                                                     const int32_t* __restrict__ nbr, const float* __restrict__ w,
                                                     int deg, int n, int64_t d, Pitch ld, float neg_lr, int lpr,
@@ -1055,8 +1061,8 @@ __global__ __launch_bounds__(T) void mix_deg_kernel(const float* X, float* Xout,
     }
     double total;
     if (DEEP)
-        total = tile_path_deep<VEC, GT, CD, T>(X, Xout, G, tab, lds_raw + tab_bytes, n, deg, ld, d / VEC, neg_lr, lpr,
-                                               1.0 / (double)n, comb_in_tile != 0);
+        total = tile_path_deep<VEC, GT, CD, T, DEEP == 1>(X, Xout, G, tab, lds_raw + tab_bytes, n, deg, ld, d / VEC, neg_lr,
+                                                          lpr, 1.0 / (double)n, comb_in_tile != 0);
     else
         total = tile_path<VEC, GT, CD, T>(X, Xout, G, tab, lds_raw + tab_bytes, n, deg, ld, d / VEC, neg_lr, lpr,
                                           1.0 / (double)n);
@@ -1752,9 +1758,10 @@ int mix_step_impl(const char* name, const float* X, int64_t ldx, float* X_out, i
     } while (0)
 #define PSGD_DEG_PICK(VEC, CD)                                                                                          \
     do {                                                                                                                \
-        if (deep) PSGD_DEG_LAUNCH(VEC, CD, (CD ? kTileThreads : kDeepThreads), true);                                   \
-        else if (big) PSGD_DEG_LAUNCH(VEC, CD, kTileThreads, false);                                                    \
-        else PSGD_DEG_LAUNCH(VEC, CD, kThreads, false);                                                                 \
+        if (deep && tp.lpr >= 64) PSGD_DEG_LAUNCH(VEC, CD, (CD ? kTileThreads : kDeepThreads), 1);                      \
+        else if (deep) PSGD_DEG_LAUNCH(VEC, CD, (CD ? kTileThreads : kDeepThreads), 2);                                 \
+        else if (big) PSGD_DEG_LAUNCH(VEC, CD, kTileThreads, 0);                                                        \
+        else PSGD_DEG_LAUNCH(VEC, CD, kThreads, 0);                                                                     \
     } while (0)
         if (vec4 && want_cd) PSGD_DEG_PICK(4, true);
         else if (vec4) PSGD_DEG_PICK(4, false);

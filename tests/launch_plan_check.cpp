@@ -122,39 +122,47 @@ int main() {
                             CHECK(p.tab_bytes >= (size_t)n * deg * 8 && p.tab_bytes % 16 == 0, "slot table size");
                             CHECK(p.tile_bytes >= (size_t)n * p.lpr * vec * 4 && p.tile_bytes % 16 == 0, "tile size");
                             const size_t slots = p.lpr <= 64 ? threads / 64 : nrg;
-                            CHECK(p.comb_bytes == (cd ? slots * p.lpr * vec * (p.lpr >= 64 ? 12 : 8) : 0), "merge slots");
+                            CHECK(p.comb_bytes == (cd ? slots * p.lpr * vec * 8 : 0), "merge slots");
                             CHECK(p.total == p.tab_bytes + 2 * p.tile_bytes + p.comb_bytes && !p.comb_in_tile, "total");
                         }
         }
     CHECK(tile_plan(128, 3, 4, 512, true, large, 0, 8).lpr == 32, "n = 128: 512-byte row segments");
-    CHECK(tile_plan(70, 3, 4, 512, true, large, 0, 8).lpr == 32, "n = 70 with the distance: 512-byte row segments");
-    CHECK(tile_plan(70, 3, 4, 512, false, large, 0, 8).lpr == 64, "n = 70 without it: 1 KB row segments, two batches");
+    CHECK(tile_plan(70, 3, 4, 512, true, large, 0, 8).lpr == 64, "n = 70, several batches per tile: 1 KB row segments");
+    CHECK(tile_plan(75, 3, 4, 512, true, large, 0, 8).lpr == 32, "n = 75 with the distance: 512-byte row segments");
     // one-batch form of the 1024-lane workgroup: whole-wavefront rows, at most 4 rows per lane, the merge slots
     // (48 KB at 16 B per lane) inside the consumed tile buffer when they do not fit beside the two tiles
-    for (int n : {1, 2, 3, 5, 8, 9, 16, 20, 32, 48, 64, 65, 128})
+    for (int n : {1, 2, 3, 5, 8, 9, 16, 20, 32, 48, 64, 65, 70, 128, 200, 256, 257, 512})
         for (int deg : {1, 3, 5, 13, 32})
             for (int vec : {1, 4})
-                for (bool cd : {false, true}) {
-                    const TilePlan p = tile_plan(n, deg, vec, 1024, cd, large, 0, 4, true);
-                    if (p.lpr == 0) {
-                        CHECK(n > 64, "n=%d deg=%d vec=%d cd=%d has no one-batch plan", n, deg, vec, (int)cd);
-                        continue;
+                for (int threads : {512, 1024})
+                    for (bool cd : {false, true}) {
+                        if ((long)n * deg > 4096) continue;
+                        const int rpb = threads == 1024 ? 4 : 8;
+                        const TilePlan p = tile_plan(n, deg, vec, threads, cd, large, 0, rpb, true);
+                        if (p.lpr == 0) {
+                            CHECK(n > 256 || (long)n * deg * 8 > 24 * 1024, "n=%d deg=%d vec=%d cd=%d has no one-batch plan", n, deg, vec, (int)cd);
+                            continue;
+                        }
+                        const int nrg = threads / p.lpr;
+                        CHECK(p.lpr >= 16 && (p.lpr & (p.lpr - 1)) == 0 && (n + nrg - 1) / nrg <= rpb, "one-batch shape: lpr %d", p.lpr);
+                        CHECK(nrg <= 64, "n=%d: %d row groups, the lanes of a column would not fit a wavefront", n, nrg);
+                        CHECK(p.comb_bytes == (cd ? (size_t)nrg * p.lpr * vec * 12 : 0), "one-batch merge slots");
+                        CHECK(p.total == p.tab_bytes + 2 * p.tile_bytes + (p.comb_in_tile ? 0 : p.comb_bytes) && p.total <= large,
+                              "one-batch total");
+                        CHECK(!p.comb_in_tile || (cd && p.comb_bytes <= p.tile_bytes), "merge slots inside a tile buffer must fit it");
                     }
-                    const int nrg = 1024 / p.lpr;
-                    CHECK(p.lpr >= 64 && (p.lpr & (p.lpr - 1)) == 0 && (n + nrg - 1) / nrg <= 4, "one-batch shape: lpr %d", p.lpr);
-                    CHECK(nrg <= n || n < 4, "n=%d: %d row groups", n, nrg);
-                    CHECK(p.comb_bytes == (cd ? (size_t)nrg * p.lpr * vec * 12 : 0), "one-batch merge slots");
-                    CHECK(p.total == p.tab_bytes + 2 * p.tile_bytes + (p.comb_in_tile ? 0 : p.comb_bytes) && p.total <= large,
-                          "one-batch total");
-                    CHECK(!p.comb_in_tile || (cd && p.comb_bytes <= p.tile_bytes), "merge slots inside a tile buffer must fit it");
-                }
     {
         const TilePlan p = tile_plan(64, 13, 4, 1024, true, large, 0, 4, true);
         CHECK(p.lpr == 64 && p.comb_in_tile, "n = 64, 13 slots, distance: 1 KB row segments, merge slots in the tile");
         CHECK(tile_plan(64, 3, 4, 1024, false, large, 0, 4, true).lpr == 64, "n = 64 without the distance");
+        CHECK(tile_plan(64, 13, 4, 512, true, large, 0, 8, true).lpr == 64 && !tile_plan(64, 13, 4, 512, true, large, 0, 8, true).comb_in_tile,
+              "n = 64 with the distance at 512 lanes: merge slots beside the tiles");
         CHECK(tile_plan(16, 3, 4, 1024, true, large, 0, 4, true).lpr == 256, "n = 16: 4 KB row segments, 4 rows per lane");
         CHECK(tile_plan(8, 3, 4, 1024, true, large, 0, 4, true).lpr == 512, "n = 8: 8 KB row segments");
-        CHECK(tile_plan(65, 3, 4, 1024, false, large, 0, 4, true).lpr == 0, "n = 65: no one-batch plan");
+        CHECK(tile_plan(128, 3, 4, 1024, false, large, 0, 4, true).lpr == 32, "n = 128: 512-byte row segments, 32 row groups of 4 rows");
+        CHECK(tile_plan(128, 3, 4, 512, true, large, 0, 8, true).lpr == 32, "n = 128 with the distance: 16 row groups of 8 rows");
+        CHECK(tile_plan(256, 3, 4, 1024, false, large, 0, 4, true).lpr == 16, "n = 256: 256-byte row segments");
+        CHECK(tile_plan(257, 3, 4, 1024, false, large, 0, 4, true).lpr == 0, "n = 257: no one-batch plan");
         CHECK(!tile_plan(64, 3, 1, 1024, true, large, 0, 4, true).comb_in_tile, "4 B per lane: the merge slots fit beside the tiles");
     }
     if (failures) return 1;

@@ -944,7 +944,28 @@ def test_tiled_kernel_long_rows_every_element(psgd, n, d, kind, gkind):
     assert psgd.device_status() == 0
 
 
-@pytest.mark.parametrize("n", [16, 64])
+@pytest.mark.parametrize("n,kind,gkind", [(200, "deg5", "bf16"), (256, "two_rings", "f32")])
+def test_tiled_kernel_long_rows_many_learners(psgd, n, kind, gkind):
+    """More than 128 learners on long rows: 256-byte row segments (16 lanes per row), four row groups per
+    wavefront, in the one-batch form; every element and the fused distance against the oracle."""
+    d = 1_580_004
+    rng = np.random.default_rng(n)
+    nbr, w = _two_rings_table(n) if kind == "two_rings" else _perm_sum_table(n, 5, rng)
+    X = inp.host_normal_f32((n, d), 1.0, 720 + n)
+    G = inp.host_normal_f32((n, d), 0.5, 730 + n)
+    if gkind == "bf16":
+        G = inp.f32_to_bf16_bits(G)
+    want = orc.mix_step(X, G, orc.densify(nbr, w), 0.2)
+    got, c = run_step_cd(psgd, X, G, nbr, w, 0.2)
+    assert_close(got, want)
+    c_ref = orc.consensus_dist(got)
+    assert abs(c - c_ref) <= REL * c_ref
+    got_plain = run_step(psgd, X, G, nbr, w, 0.2)                # the build without the distance
+    assert np.array_equal(got_plain.view(np.uint32), got.view(np.uint32))
+    assert psgd.device_status() == 0
+
+
+@pytest.mark.parametrize("n", [16, 64, 128])
 def test_tiled_kernel_long_rows_distance_corner_cases(psgd, n):
     """The row groups of the large tiled kernel each measure against their own pivot and the merge brings
     them to a common one: replicas far from the origin and close together must still give the distance to
