@@ -652,11 +652,15 @@ __device__ __forceinline__ void tile_finish(const TileCtx<VEC>& c, double* comb,
 template <int VEC, int T>
 __device__ __forceinline__ void tile_finish_own(const TileCtx<VEC>& c, double* comb, float* combp, int live_cols,
                                                 TileStats<VEC>& st, double inv_n, double& total) {
-    const size_t mine = (size_t)(c.rg * c.lpr + c.lane) * VEC;
+    // live_cols: the lanes of the tile that own a column group (all of them except in the ragged last tile)
+    // slot of row group q, column k of lane l: (q VEC + k) lpr + l, so that the lanes of a wavefront write
+    // neighbouring words (no bank conflicts); the merge below numbers the tile's columns in the same order
+    const int cols = c.lpr * VEC;
+    const size_t mine = (size_t)c.rg * cols + c.lane;
 #pragma unroll
     for (int k = 0; k < VEC; ++k) {
-        comb[mine + k] = st.a[k];
-        combp[mine + k] = st.pivf[k];
+        comb[mine + k * c.lpr] = st.a[k];
+        combp[mine + k * c.lpr] = st.pivf[k];
     }
     total += st.sq;
     lds_barrier();
@@ -669,9 +673,9 @@ __device__ __forceinline__ void tile_finish_own(const TileCtx<VEC>& c, double* c
     // reads are issued before the first is used, and a slot that does not count enters with weight 0.
     const int parts = c.nrg >= VEC ? c.nrg / VEC : 1;        // a power of two; the lanes of a column sit side by side in one wavefront
     const int each = c.nrg / parts;                          // row groups per lane: min(nrg, VEC)
-    const int cols = c.lpr * VEC;
-    for (int idx = threadIdx.x; idx < live_cols * VEC * parts; idx += T) {
+    for (int idx = threadIdx.x; idx < cols * parts; idx += T) {
         const int col = idx / parts, part = idx % parts;
+        const bool live = (col & (c.lpr - 1)) < live_cols;   // a column of a lane beyond the ragged end counts for nothing
         double aq[VEC], md[VEC];
         float pq[VEC];
         const float p0f = combp[col];                        // row group 0 owns row 0: its pivot is the common one
@@ -706,7 +710,7 @@ __device__ __forceinline__ void tile_finish_own(const TileCtx<VEC>& c, double* c
             at += __shfl_xor(at, off, 64);
             corr += __shfl_xor(corr, off, 64);
         }
-        if (part == 0) total += corr - at * at * inv_n;
+        if (part == 0 && live) total += corr - at * at * inv_n;
     }
     lds_barrier();                                     // the merge slots are free again
 }
