@@ -307,15 +307,16 @@ def main():
     torch.cuda.synchronize()
     fused = not (args.unfused or args.no_consensus)
 
-    def widen(nbr3):
+    def widen(nbr3, k=None):
         """K-slot table on the same ring: follow the right (left) pointers (K-1)/2 times."""
+        k = deg if k is None else k
         left, right = nbr3[:, 1], nbr3[:, 2]
         cols, lo, hi = [nbr3[:, 0]], nbr3[:, 0], nbr3[:, 0]
-        for _ in range((deg - 1) // 2):
+        for _ in range((k - 1) // 2):
             lo, hi = left[lo], right[hi]
             cols += [lo, hi]
         return (np.ascontiguousarray(np.stack(cols, axis=1), dtype=np.int32),
-                np.full((n, deg), 1.0 / deg, dtype=np.float32))
+                np.full((nbr3.shape[0], k), 1.0 / k, dtype=np.float32))
 
     def split_in_two(nbr3):
         """The same learners on two disjoint rings: every learner's neighbours become its neighbours' neighbours
@@ -542,7 +543,7 @@ def main():
              "value": w_.n * w_.d / (avg * 1e-3), "unit": "updates/s",
              "achieved_GBps": gbs, "frac": gbs / HBM_PEAK_GBS, "launches": 5}
         r.update(extra)
-        log("  %-34s %8.3f ms  %7.1f GB/s  %5.1f %% of peak" % (label, avg, gbs, 100 * gbs / HBM_PEAK_GBS))
+        log("  %-44s %8.3f ms  %7.1f GB/s  %5.1f %% of peak" % (label, avg, gbs, 100 * gbs / HBM_PEAK_GBS))
         return r
 
     def reference_streams(w_, Xr, Yr, Gr, layout):
@@ -580,6 +581,20 @@ def main():
             ms = timed(lambda s_: psgd.mix_step(Xa, Xa, Ga, tab[0], tab[1], wl.lr, stream=s_, cdist_out=cd1))
             legs["pitched_in_place"] = leg("pitched, in place", wl, mix_bytes, ms, layout="pitched", in_place=True,
                                            entry_point="psgd_mix_step_ex")
+        if not wl.delay and n % 2 == 0 and n >= 13:
+            # ---- tables that are not one ring (the LDS-tiled kernel), and the distance as a pass of its own
+            nb3, w3 = psgd.build_mixing(wl.topology, n, wl.seed_perm, total - 1)
+            for key, label, (nb_, ww_) in (
+                    ("tiled_two_rings_pitched", "two disjoint rings (tiled kernel)", (split_in_two(nb3), w3)),
+                    ("tiled_degree13_pitched", "13 neighbours per learner (tiled kernel)", widen(nb3, 13))):
+                nb_, ww_ = torch.from_numpy(nb_).to(dev), torch.from_numpy(ww_).to(dev)
+                ms = timed(lambda s_: psgd.mix_step(Xa, Ya, Ga, nb_, ww_, wl.lr, stream=s_, cdist_out=cd1))
+                legs[key] = leg(label, wl, mix_bytes, ms, layout="pitched", in_place=False,
+                                entry_point="psgd_mix_step_ex" if nb_.shape[1] == 3 else "psgd_mix_step_deg",
+                                table_degree=int(nb_.shape[1]))
+            ms = timed(lambda s_: psgd.consensus_dist_async(Ya, cd1, stream=s_))
+            legs["consensus_alone_pitched"] = leg("consensus distance alone (4 B per element)", wl, 4 * n * d, ms,
+                                                  layout="pitched", entry_point="psgd_consensus_dist_async")
         del Xa, Ya, Ga
         # ---- the plain dense [n, d] arrays of the entry points the baseline names
         del X, Y, Gs, X_prev, views, pool, noise, delayed

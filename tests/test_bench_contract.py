@@ -75,8 +75,9 @@ def test_variants_run_and_report(flags):
 
 @pytest.mark.gpu
 def test_default_form_reports_the_legs_it_is_read_against():
-    """Without flags the line also carries the same step in place and on dense arrays, the reference streams
-    (read-only, write-only, x + a g in the step kernel's access pattern) and the runtime's device copy."""
+    """Without flags the line also carries the same step in place and on dense arrays, tables that are not one ring
+    (the tiled kernel), the distance as a pass of its own, the reference streams (read-only, write-only, x + a g
+    in the step kernel's access pattern) and the runtime's device copy."""
     torch = pytest.importorskip("torch")
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
@@ -84,7 +85,8 @@ def test_default_form_reports_the_legs_it_is_read_against():
                        capture_output=True, text=True, timeout=600)
     assert p.returncode == 0, p.stderr[-2000:]
     r = json.loads(p.stdout.strip())
-    for key in ("pitched_out_of_place", "pitched_in_place", "dense_out_of_place", "dense_in_place"):
+    for key in ("pitched_out_of_place", "pitched_in_place", "dense_out_of_place", "dense_in_place",
+                "tiled_two_rings_pitched", "tiled_degree13_pitched", "consensus_alone_pitched"):
         leg = r["legs"][key]
         assert 0.2 < leg["frac"] < 1.0 and leg["avg_launch_ms"] > 0 and leg["workload"].startswith("cfg2"), (key, leg)
     for block in ("reference_streams", "reference_streams_dense"):
