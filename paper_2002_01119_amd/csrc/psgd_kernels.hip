@@ -16,7 +16,7 @@
 //     run in place.
 // Tables live in device memory and are validated and classified (one ring or not) by the kernels.
 // Workgroups are persistent, so table staging is paid once per launch.  On long rows the workgroups are
-// large (768 lanes for the ring walk, 512 for the tiled path), one per compute unit; the ring walk's
+// large (768 lanes for the ring walk, 512 or 1024 for the tiled path), one per compute unit; the ring walk's
 // wavefronts sweep the rows in lockstep, a barrier per batch of rows: the HBM then sees one 12 KB burst
 // per row instead of twelve separate 1 KB requests, which is worth 1-3 % of the peak for kernels that
 // write.
@@ -428,11 +428,15 @@ __device__ __forceinline__ void ring_walk(const float* xc, float* oc, const GT* 
 // The workgroup's T lanes form T / lpr row groups of lpr lanes; a tile is n rows by lpr column groups and lives
 // in LDS, so a neighbour read is an LDS read and every X element crosses the HBM interface once.  Lane (rg,
 // lane) produces rows rg, rg + nrg, ... of column group `lane` of the tile.  Two tile buffers alternate: while
-// the rows of tile t are computed from one, the X rows of the workgroup's next tile travel from HBM into
-// registers and are stored into the other at the end of each batch of rows; the gradients of the following
-// batch travel at the same time.  One barrier per tile separates "everyone has finished reading this buffer and
-// writing the other" from the next round.  A tile is complete in LDS before its first output is stored, and
-// different tiles own different columns, so X_out may alias X.
+// the rows of tile t are computed from one, the X rows of the workgroup's next tile are written into the
+// other.  A barrier per tile separates "everyone has finished reading this buffer and writing the other" from
+// the next tile.  A tile is complete in LDS before its first output is stored, and different tiles own
+// different columns, so X_out may alias X.
+//
+// Two forms.  tile_path_deep (long rows, up to 256 learners): the tile's rows are one batch, every memory
+// operation is unconditional, and a lane reloads each of its registers the moment its value has been used (see
+// there).  tile_path (short rows; long rows with more learners): several batches per tile, the next tile's
+// batch travelling while this tile's is computed, loads under conditions.
 //
 // Per output the slots are taken in table order, acc = w0 * x0, one fma per further slot, then the gradient
 // term (for 3 slots exactly mix_one's order).  The slot loop is the latency-critical part (a table read, then
@@ -440,10 +444,12 @@ __device__ __forceinline__ void ring_walk(const float* xc, float* oc, const GT* 
 // independent chains hide each other's LDS round trips.
 //
 // With CD the distance of the outputs is gathered in the same pass.  The rows of one column group are spread
-// over the row groups, so all of them measure against ONE pivot, the output of row 0, which every row group
-// computes for itself (bit-identical: same tile, same table, same gradient bits).  The squares then add up lane
-// by lane and only the plain sums need merging per column: across the row groups that share a wavefront by
-// shuffles, across wavefronts through one LDS slot each, summed in fixed order.
+// over the row groups.  tile_path: all of them measure against ONE pivot, the output of row 0, which every row
+// group computes for itself (bit-identical: same tile, same table, same gradient bits); the squares then add up
+// lane by lane and only the plain sums need merging per column: across the row groups that share a wavefront by
+// shuffles, across wavefronts through one LDS slot each, summed in fixed order (tile_finish).  tile_path_deep:
+// every row group measures against its own first output and the merge brings the sums to row group 0's pivot
+// exactly (tile_finish_own).
 // ---------------------------------------------------------------------------------------
 // The value of the lane whose number differs in bit 0 (CTRL 0xB1: quad order 1,0,3,2) or bit 1 (0x4E: 2,3,0,1),
 // moved inside the vector unit (no LDS round trip).  All four lanes of a quad must be active.
@@ -455,9 +461,10 @@ __device__ __forceinline__ double lane_xor_quad(double v) {
     return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
 }
 
-// The large workgroup is alone on its compute unit and may use 256 registers per lane: 8 rows in flight (8
-// wavefronts x 8 rows cover n = 64 at once).  The small one, which serves short rows (launches bound by latency,
-// several workgroups per CU) and shares the 3-slot kernel with the ring walk there, stays frugal.
+// The large workgroups are alone on their compute unit: 512 lanes with up to 256 registers per lane (8
+// wavefronts x 8 rows cover n = 64 at once), or 1024 lanes with up to 128 (16 x 4).  The small one, which serves
+// short rows (launches bound by latency, several workgroups per CU) and shares the 3-slot kernel with the ring
+// walk there, stays frugal.
 template <int T> struct TileShape {
     static constexpr int RB = T > 512 ? 4 : T > 256 ? 8 : 2;   // rows per lane and batch
     static constexpr int SB = T == 512 ? 3 : 2;   // rows whose slot chains advance together (two slots per trip each);
