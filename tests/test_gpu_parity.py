@@ -965,6 +965,30 @@ def test_tiled_kernel_long_rows_many_learners(psgd, n, kind, gkind):
     assert psgd.device_status() == 0
 
 
+@pytest.mark.parametrize("n,deg,gkind", [(64, 32, "f32"), (64, 32, "bf16"), (128, 32, "bf16")])
+def test_tiled_kernel_long_rows_widest_tables(psgd, n, deg, gkind):
+    """32 slots per row on long rows: the slot table takes 16 KB (32 KB for 128 learners) of LDS, so the merge
+    slots of the distance no longer fit beside the two tile buffers and live in the buffer that has just been
+    consumed (n = 64), or the rows get narrower (n = 128).  Every element and the distance against the oracle."""
+    d = 1_580_004
+    rng = np.random.default_rng(n + deg)
+    nbr, w = _perm_sum_table(n, deg, rng)
+    X = inp.host_normal_f32((n, d), 1.0, 740 + n)
+    G = inp.host_normal_f32((n, d), 0.5, 750 + n)
+    if gkind == "bf16":
+        G = inp.f32_to_bf16_bits(G)
+    want = orc.mix_step(X, G, orc.densify(nbr, w), 0.2)
+    got, c = run_step_cd(psgd, X, G, nbr, w, 0.2)
+    assert_close(got, want, rel=REL * deg / 4)                   # deg + 1 roundings instead of 4
+    c_ref = orc.consensus_dist(got)
+    assert abs(c - c_ref) <= REL * c_ref
+    got_ip, c_ip = run_step_cd(psgd, X, G, nbr, w, 0.2, in_place=True)
+    assert np.array_equal(got_ip.view(np.uint32), got.view(np.uint32)) and c_ip == c
+    got_plain = run_step(psgd, X, G, nbr, w, 0.2)                # the build without the distance
+    assert np.array_equal(got_plain.view(np.uint32), got.view(np.uint32))
+    assert psgd.device_status() == 0
+
+
 @pytest.mark.parametrize("n", [16, 64, 128])
 def test_tiled_kernel_long_rows_distance_corner_cases(psgd, n):
     """The row groups of the large tiled kernel each measure against their own pivot and the merge brings
