@@ -911,10 +911,21 @@ def _two_rings_table(n):
     return nbr, np.tile(np.asarray([0.5, 0.25, 0.25], dtype=np.float32), (n, 1))
 
 
-@pytest.mark.parametrize("n,d", [(64, 1_600_004), (64, 1_572_867), (128, 1_600_004), (33, 1_700_004), (8, 1_800_004),
-                                 (70, 1_600_004), (16, 1_900_004), (5, 2_000_004), (48, 1_600_003)])
-@pytest.mark.parametrize("kind", ["two_rings", "deg5", "deg13"])
-@pytest.mark.parametrize("gkind", ["f32", "bf16"])
+_LONG_ROW_CASES = (
+    # the main shape, every table kind and both gradient types
+    [(64, 1_600_004, k, g) for k in ("two_rings", "deg5", "deg13") for g in ("f32", "bf16")]
+    # the other shapes: two or three (table kind, gradient type) pairs each
+    + [(64, 1_572_867, "two_rings", "f32"), (64, 1_572_867, "deg13", "bf16"),
+       (128, 1_600_004, "two_rings", "bf16"), (128, 1_600_004, "deg5", "f32"), (128, 1_600_004, "deg13", "bf16"),
+       (33, 1_700_004, "deg5", "f32"), (33, 1_700_004, "deg13", "bf16"),
+       (8, 1_800_004, "two_rings", "f32"), (8, 1_800_004, "deg5", "bf16"), (8, 1_800_004, "deg13", "f32"),
+       (70, 1_600_004, "two_rings", "f32"), (70, 1_600_004, "deg13", "bf16"),
+       (16, 1_900_004, "two_rings", "bf16"), (16, 1_900_004, "deg5", "f32"),
+       (5, 2_000_004, "deg5", "f32"), (5, 2_000_004, "deg13", "bf16"),
+       (48, 1_600_003, "two_rings", "f32"), (48, 1_600_003, "deg5", "bf16")])
+
+
+@pytest.mark.parametrize("n,d,kind,gkind", _LONG_ROW_CASES)
 def test_tiled_kernel_long_rows_every_element(psgd, n, d, kind, gkind):
     """Rows long enough for the large-workgroup tiled kernels: the 1024-lane one-batch form for n <= 64 (merge
     slots of the distance inside the consumed tile buffer at 16 B per lane; wider rows for n = 16, 8, 5; an odd
