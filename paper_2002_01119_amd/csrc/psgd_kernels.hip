@@ -207,14 +207,14 @@ int resident_per_cu(const void* fn, size_t lds_bytes, int threads = kThreads) {
         int occ;
     };
     static std::mutex mu;
-    static Entry cache[32];
+    static Entry cache[128];
     static int used = 0;
     std::lock_guard<std::mutex> lock(mu);
     for (int i = 0; i < used; ++i)
         if (cache[i].fn == fn && cache[i].lds == lds_bytes) return cache[i].occ;
     int q = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&q, fn, threads, lds_bytes) != hipSuccess || q < 1) q = 1;
-    if (used < 32) cache[used++] = Entry{fn, lds_bytes, q};
+    if (used < 128) cache[used++] = Entry{fn, lds_bytes, q};
     return q;
 }
 
@@ -229,11 +229,26 @@ bool scalar_overlaps(const double* p, const void* B, int64_t ldb, size_t rb, int
 }
 
 // A workgroup gets 64 KB of dynamic LDS by default; a kernel that is to be launched with more is opted in.
+// Once per kernel and device (the attribute belongs to the kernel's code object on that device).
 int allow_lds(const void* fn, size_t lds_bytes) {
     if (lds_bytes <= 64 * 1024 - 256) return PSGD_OK;
+    struct Entry {
+        const void* fn;
+        int device;
+    };
+    static std::mutex mu;
+    static Entry done[128];
+    static int used = 0;
+    int device = 0;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    std::lock_guard<std::mutex> lock(mu);
+    for (int i = 0; i < used; ++i)
+        if (done[i].fn == fn && done[i].device == device) return PSGD_OK;
     // the most this library ever asks for (the kernels' few hundred bytes of static LDS come on top of it)
-    const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsCapLarge);
+    e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsCapLarge);
     if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(MaxDynamicSharedMemorySize)");
+    if (used < 128) done[used++] = Entry{fn, device};
     return PSGD_OK;
 }
 constexpr int kLaunchRefused = INT32_MIN;

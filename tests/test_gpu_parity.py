@@ -675,6 +675,49 @@ def test_steps_captured_in_a_hip_graph_replay_exactly(psgd):
         assert abs(psgd.consensus_dist(out) - c_eager[-1].item()) <= 1e-9 * c_eager[-1].item()
 
 
+def test_long_row_kernels_captured_in_a_hip_graph_replay_exactly(psgd):
+    """The same on rows long enough for the large workgroups: the ring walk (with the tiled kernel enqueued
+    behind it), a 5-slot table through the tiled kernel (more than 64 KB of LDS) and global averaging, every
+    one with the fused distance, captured once after an eager pass and replayed between eager work."""
+    n, d = 16, 1_600_004
+    rng = np.random.default_rng(5)
+    X0 = dev(inp.host_normal_f32((n, d), 1.0, 23))
+    G = dev(inp.host_normal_f32((n, d), 0.1, 24))
+    ring = [dev(t) for t in psgd.build_mixing(psgd.TOPO_RAND_RING, n, 34, 0)]
+    deg5 = [dev(t) for t in _perm_sum_table(n, 5, rng)]
+    c_eager = torch.zeros(3, dtype=torch.float64, device="cuda:0")
+    c_graph = torch.zeros(3, dtype=torch.float64, device="cuda:0")
+    A, B = X0.clone(), torch.empty(n, d, device="cuda:0")
+
+    def run(cbuf, stream=None):
+        psgd.mix_step(A, B, G, ring[0], ring[1], 0.05, cdist_out=cbuf[0:1], stream=stream)
+        psgd.mix_step(B, A, G, deg5[0], deg5[1], 0.05, cdist_out=cbuf[1:2], stream=stream)
+        psgd.mix_full(A, B, G, 0.05, cdist_out=cbuf[2:3], stream=stream)
+        return B
+
+    run(c_eager)
+    torch.cuda.synchronize()
+    want = B.clone()
+    assert c_eager[0].item() > c_eager[1].item() > 0 and c_eager[2].item() > 0
+    s = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    A.copy_(X0)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g, stream=s):
+        out = run(c_graph, stream=torch.cuda.current_stream())
+    for rep in range(3):
+        A.copy_(X0)
+        B.fill_(float("nan"))
+        c_graph.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), rep
+        assert torch.equal(c_graph, c_eager), rep
+        assert abs(psgd.consensus_dist(out) - c_eager[-1].item()) <= 1e-9 * c_eager[-1].item()
+    assert psgd.device_status() == 0
+
+
 # ------------------------------------------------------------------------- tables built on the device
 @pytest.mark.parametrize("n", [1, 2, 3, 5, 8, 64, 128, 257, 512])
 def test_device_built_tables_bit_identical_to_oracle(psgd, n):
