@@ -21,6 +21,7 @@ Prints ONE JSON line on stdout; progress and per-kernel detail go to stderr.
 import argparse
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -160,10 +161,12 @@ def main():
     ap.add_argument("--no-extra-legs", action="store_true",
                     help="skip the measurements that follow the timed region (in-place, dense layout, other workloads, "
                          "reference streams, device copy)")
-    ap.add_argument("--layout", choices=["pitched", "probe", "dense"], default="pitched",
+    ap.add_argument("--layout", choices=["pitched", "spread", "probe", "dense"], default="pitched",
                     help="where the arrays live in HBM: 'pitched' interleaves the rows of all arrays across most of "
-                         "the device (psgd_mix_step_ex), 'probe' keeps dense arrays but places X / X_out on the "
-                         "windows of one pool where the step runs fastest, 'dense' is one plain tensor per array")
+                         "the device (psgd_mix_step_ex), 'spread' is the same layout on psgd_spread_alloc memory "
+                         "(rows physically as far apart, only the rows resident), 'probe' keeps dense arrays but "
+                         "places X / X_out on the windows of one pool where the step runs fastest, 'dense' is one "
+                         "plain tensor per array")
     ap.add_argument("--span-fraction", type=float, default=0.65,
                     help="pitched layout: fraction of device memory the row slots are spread over")
     ap.add_argument("--g-apart", action="store_true",
@@ -214,9 +217,10 @@ def main():
     def gdtype(w_):
         return torch.bfloat16 if w_.g_dtype == "bf16" else torch.float32
 
-    def pitched_buffers(w_, in_place, with_delay_buffers, settle=True):
+    def pitched_buffers(w_, in_place, with_delay_buffers, settle=True, spread=False):
         """Rows of every array interleaved across most of the HBM (placement.pitched_layout):
-        slot i = [X_i | Y_i | (Xprev_i | noise_i) | G0_i | G1_i], slots `pitch` bytes apart."""
+        slot i = [X_i | Y_i | (Xprev_i | noise_i) | G0_i | G1_i], slots `pitch` bytes apart.  With `spread` the
+        slots come from psgd_spread_alloc: as far apart physically, but nothing between them stays allocated."""
         free, total_mem = torch.cuda.mem_get_info()
         specs = [("X", torch.float32)] + ([] if in_place else [("Y", torch.float32)])
         if with_delay_buffers:
@@ -224,6 +228,13 @@ def main():
         gspecs = [("G0", gdtype(w_)), ("G1", gdtype(w_))]
         span = min(int(args.span_fraction * total_mem), free - (8 << 30))
         pools = []
+        if spread:
+            views, owner, pitch = plc.spread_layout(w_.n, w_.d, specs + gspecs, span, dev)
+            rep = {"layout": "spread", "pitch_GB": pitch / 1e9, "span_GB": w_.n * pitch / 1e9,
+                   "pool_allocated_GB": owner.resident_bytes() / 1e9,
+                   "data_resident_GB": sum(v.shape[0] * v.shape[1] * v.element_size() for v in views.values()) / 1e9,
+                   "arrays": list(views.keys()), "gradients_in_own_pool": False}
+            return views, [owner], rep
         if args.g_apart:
             gbytes = 2 * w_.n * w_.d * torch.empty((), dtype=gdtype(w_)).element_size()
             views, pool, pitch = plc.pitched_layout(w_.n, w_.d, specs, span - gbytes - (1 << 30), dev, settle=settle)
@@ -248,11 +259,12 @@ def main():
         return (inp.device_normal_bf16 if wl.g_dtype == "bf16" else inp.device_normal_f32)(
             (n, d), wl.sigma_g, wl.seed_g + i, dev)
 
-    if args.layout == "pitched":
+    if args.layout in ("pitched", "spread"):
         try:
-            views, pool, layout_report = pitched_buffers(wl, args.in_place, wl.delay)
-            log("pitched layout: %d slots %.3f GB apart, pool %.1f GB for %.1f GB of data"
-                % (n, layout_report["pitch_GB"], layout_report["pool_allocated_GB"], layout_report["data_resident_GB"]))
+            views, pool, layout_report = pitched_buffers(wl, args.in_place, wl.delay, spread=args.layout == "spread")
+            log("%s layout: %d slots %.3f GB apart, %.1f GB allocated for %.1f GB of data"
+                % (args.layout, n, layout_report["pitch_GB"], layout_report["pool_allocated_GB"],
+                   layout_report["data_resident_GB"]))
         except torch.OutOfMemoryError:
             log("pitched layout does not fit; falling back to dense tensors")
             views, layout_report = None, {"layout": "dense (pitched did not fit)"}
@@ -640,6 +652,28 @@ def main():
                                                        ms, layout="pitched", in_place=False, entry_point="psgd_mix_step_ex")
                 del v_, p_
                 torch.cuda.empty_cache()
+        # ---- the headline's workload with only its data resident: rows physically spread by psgd_spread_alloc
+        # instead of living in a pool that spans the device.  In a process of its own: the order in which the
+        # driver hands out physical memory, which that layout relies on, is only in address order in a process
+        # that has not freed large allocations before (64.8-66 % in this process at this point, 76-77.6 % fresh).
+        torch.cuda.empty_cache()
+        try:
+            child = subprocess.run([sys.executable, os.path.abspath(__file__), "--workload", str(args.workload),
+                                    "--layout", "spread", "--no-extra-legs", "--no-cpu-baseline", "--steps", "5",
+                                    "--warmup", "2", "--span-fraction", str(args.span_fraction)],
+                                   capture_output=True, text=True, timeout=300)
+            r_ = json.loads(child.stdout.strip().splitlines()[-1])
+            roof_, lay_ = r_["roofline"], r_["config"]["hbm_layout"]
+            legs["spread_fresh_process"] = {
+                "workload": wl.name, "avg_launch_ms": roof_["avg_launch_ms"], "value": r_["value"], "unit": "updates/s",
+                "achieved_GBps": roof_["achieved"], "frac": roof_["frac"], "launches": 5, "layout": "spread",
+                "in_place": False, "entry_point": "psgd_mix_step_ex", "allocated_GB": lay_["pool_allocated_GB"],
+                "pitch_GB": lay_["pitch_GB"], "command": "bench.py --layout spread --no-extra-legs --steps 5 --warmup 2"}
+            log("  %-44s %8.3f ms  %7.1f GB/s  %5.1f %% of peak  (%.1f GB allocated)"
+                % ("spread rows, only the data resident", roof_["avg_launch_ms"], roof_["achieved"], 100 * roof_["frac"],
+                   lay_["pool_allocated_GB"]))
+        except Exception as exc:                                      # a leg, not the measurement: report and go on
+            log("  spread leg skipped: %r" % (exc,))
         result["legs"] = legs
         if psgd.device_status() != 0:
             log("bench.py: a kernel flagged an invalid mixing table")

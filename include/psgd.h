@@ -296,6 +296,26 @@ int psgd_reference_stream(int kind, const float* X, int64_t ldx, float* X_out, i
                           const void* G, int64_t ldg, int g_is_bf16, int n, int64_t d, float a, void* stream);
 
 /*
+ * psgd_spread_alloc / psgd_spread_free - placement support, not a step of the method: device memory for the
+ * rows of the replica arrays that is spread out PHYSICALLY while only the rows themselves stay resident.
+ * On MI355X a kernel that writes many gigabytes runs at a rate that depends on where the written memory
+ * lies physically (rows a few GB apart: 87 % of the HBM peak for stores; the same rows back to back: 68 %).
+ *
+ * Reserves one address range of n * pitch bytes on the current device and backs slot i, the bytes
+ * [i * pitch, i * pitch + slot), with physical memory; slot_bytes and pitch_bytes are rounded up to the
+ * allocation granularity, the pitch used is returned in *pitch_out and the start of the range in *base_out.
+ * The physical memory of the slots is taken in turn with chunks of the size of the gaps between them, and
+ * the gap chunks are given back before the call returns: while it runs the device must have n * pitch bytes
+ * free, afterwards n * slot bytes are in use.  Addresses between the slots are not mapped: touching them
+ * faults.  The memory is not cleared.  The caller lays out its rows inside the slots (row i of every array in
+ * slot i, say) and passes base + offset with a row pitch of pitch / element size to the *_ex entry points.
+ * psgd_spread_free(base) waits for the device and releases everything; at most 16 allocations live at a time.
+ * Errors: PSGD_EINVAL (arguments, unknown base), PSGD_EHIP (the runtime refused; nothing stays allocated).
+ */
+int psgd_spread_alloc(int n, int64_t slot_bytes, int64_t pitch_bytes, void** base_out, int64_t* pitch_out);
+int psgd_spread_free(void* base);
+
+/*
  * psgd_device_status - waits for the current device, then returns the sticky flag word that
  * kernels raise (bit 0: a mixing table held an entry outside [0, n) and the step wrote
  * nothing).  `clear` != 0 resets it.  Negative psgd_status on failure.

@@ -1,0 +1,171 @@
+// Placement support of libpsgd (host code only; not a step of the method): device memory for the rows of the
+// replica arrays whose PHYSICAL pages lie far apart, with nothing but the rows resident.
+//
+// On MI355X the rate of a kernel that writes many gigabytes depends on where the written memory lies physically:
+// 64 rows of 1 GB that lie 3 GB apart are written at 87 % of the HBM peak, the same rows back to back at 68 %, and
+// giving the back-to-back rows virtual addresses that are 3 GB apart changes nothing.  The driver hands out
+// physical memory in the order it is asked for, so the whole span is taken in chunks of ONE size (a quarter of a
+// slot: requests of one size cannot be sorted into different holes by size), the chunks under the slots are mapped
+// and all others are given back once every chunk exists.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdlib>
+#include <mutex>
+
+#include "psgd.h"
+#include "psgd_internal.h"
+
+namespace psgd {
+namespace {
+
+constexpr int kChunksPerSlot = 4;
+struct Spread {
+    void* base = nullptr;
+    int n = 0;
+    size_t slot = 0, pitch = 0, chunk = 0;
+    hipMemGenericAllocationHandle_t* handles = nullptr;   // n * kChunksPerSlot of them, malloc'ed: chunk c of slot i at [i * 4 + c]
+    int mapped = 0;                                       // handles 0 .. mapped-1 are mapped
+    int created = 0;                                      // handles 0 .. created-1 exist
+};
+constexpr int kMaxSpreads = 16;
+std::mutex g_mu;
+Spread g_spreads[kMaxSpreads];
+
+int hip_error(hipError_t e, const char* what) {
+    return fail(PSGD_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+// Undo whatever of `s` exists; keeps the first error of the caller.
+char* chunk_address(const Spread& s, int k) {
+    return static_cast<char*>(s.base) + (size_t)(k / kChunksPerSlot) * s.pitch + (size_t)(k % kChunksPerSlot) * s.chunk;
+}
+void tear_down(Spread& s) {
+    for (int k = 0; k < s.mapped; ++k) (void)hipMemUnmap(chunk_address(s, k), s.chunk);
+    for (int k = 0; k < s.created; ++k) (void)hipMemRelease(s.handles[k]);
+    if (s.base) (void)hipMemAddressFree(s.base, (size_t)s.n * s.pitch);
+    std::free(s.handles);
+    s = Spread{};
+}
+
+}  // namespace
+}  // namespace psgd
+
+extern "C" {
+
+int psgd_spread_alloc(int n, int64_t slot_bytes, int64_t pitch_bytes, void** base_out, int64_t* pitch_out) {
+    using namespace psgd;
+    clear_error();
+    if (!base_out || !pitch_out) return fail(PSGD_EINVAL, "psgd_spread_alloc: null pointer");
+    *base_out = nullptr;
+    *pitch_out = 0;
+    if (n < 1 || n > PSGD_MAX_N) return fail(PSGD_EINVAL, "psgd_spread_alloc: n=%d outside 1..%d", n, (int)PSGD_MAX_N);
+    if (slot_bytes < 1 || pitch_bytes < slot_bytes)
+        return fail(PSGD_EINVAL, "psgd_spread_alloc: slot_bytes=%lld, pitch_bytes=%lld", (long long)slot_bytes,
+                    (long long)pitch_bytes);
+    int device = 0;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return hip_error(e, "hipGetDevice");
+    hipMemAllocationProp prop = {};
+    prop.type = hipMemAllocationTypePinned;
+    prop.location.type = hipMemLocationTypeDevice;
+    prop.location.id = device;
+    size_t gran = 0;
+    e = hipMemGetAllocationGranularity(&gran, &prop, hipMemAllocationGranularityRecommended);
+    if (e != hipSuccess || gran == 0) return hip_error(e, "hipMemGetAllocationGranularity");
+    // a slot is kChunksPerSlot chunks, the pitch a whole number of chunks
+    const size_t chunk = (((size_t)slot_bytes + kChunksPerSlot - 1) / kChunksPerSlot + gran - 1) / gran * gran;
+    const size_t slot = chunk * kChunksPerSlot;
+    size_t per_pitch = ((size_t)pitch_bytes + chunk - 1) / chunk;      // chunks from one slot's start to the next
+    if (per_pitch < (size_t)kChunksPerSlot) per_pitch = kChunksPerSlot;
+    const size_t pitch = per_pitch * chunk;
+    if (pitch > (SIZE_MAX / 2) / (size_t)n) return fail(PSGD_EINVAL, "psgd_spread_alloc: address range overflows");
+    const size_t gap_chunks = per_pitch - kChunksPerSlot;
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    Spread* rec = nullptr;
+    for (int i = 0; i < kMaxSpreads; ++i)
+        if (!g_spreads[i].base) {
+            rec = &g_spreads[i];
+            break;
+        }
+    if (!rec) return fail(PSGD_EINVAL, "psgd_spread_alloc: more than %d live allocations", kMaxSpreads);
+    Spread s;
+    s.n = n;
+    s.slot = slot;
+    s.pitch = pitch;
+    s.chunk = chunk;
+    const size_t total_gaps = gap_chunks * (size_t)(n - 1);
+    s.handles = static_cast<hipMemGenericAllocationHandle_t*>(
+        std::calloc((size_t)n * kChunksPerSlot, sizeof(hipMemGenericAllocationHandle_t)));
+    hipMemGenericAllocationHandle_t* gaps = static_cast<hipMemGenericAllocationHandle_t*>(
+        std::calloc(total_gaps ? total_gaps : 1, sizeof(hipMemGenericAllocationHandle_t)));
+    if (!s.handles || !gaps) {
+        std::free(s.handles);
+        std::free(gaps);
+        return fail(PSGD_EINVAL, "psgd_spread_alloc: out of host memory");
+    }
+    size_t ngaps = 0;
+    int rc = PSGD_OK;
+    e = hipMemAddressReserve(&s.base, (size_t)n * pitch, 0, nullptr, 0);
+    if (e != hipSuccess) {
+        s.base = nullptr;
+        rc = hip_error(e, "hipMemAddressReserve");
+    }
+    // physical memory is taken here, in address order, chunk by chunk: the chunks of slot 0, those of the gap
+    // behind it, the chunks of slot 1, ...
+    for (int i = 0; rc == PSGD_OK && i < n; ++i) {
+        for (int c = 0; rc == PSGD_OK && c < kChunksPerSlot; ++c) {
+            e = hipMemCreate(&s.handles[i * kChunksPerSlot + c], chunk, &prop, 0);
+            if (e != hipSuccess) rc = hip_error(e, "hipMemCreate (slot)");
+            else s.created = i * kChunksPerSlot + c + 1;
+        }
+        for (size_t g = 0; rc == PSGD_OK && i + 1 < n && g < gap_chunks; ++g) {
+            e = hipMemCreate(&gaps[ngaps], chunk, &prop, 0);
+            if (e != hipSuccess) rc = hip_error(e, "hipMemCreate (gap)");
+            else ++ngaps;
+        }
+    }
+    hipMemAccessDesc acc = {};
+    acc.location.type = hipMemLocationTypeDevice;
+    acc.location.id = device;
+    acc.flags = hipMemAccessFlagsProtReadWrite;
+    for (int k = 0; rc == PSGD_OK && k < n * kChunksPerSlot; ++k) {
+        char* at = chunk_address(s, k);
+        e = hipMemMap(at, chunk, 0, s.handles[k], 0);
+        if (e != hipSuccess) {
+            rc = hip_error(e, "hipMemMap");
+            break;
+        }
+        s.mapped = k + 1;
+        e = hipMemSetAccess(at, chunk, &acc, 1);
+        if (e != hipSuccess) rc = hip_error(e, "hipMemSetAccess");
+    }
+    for (size_t g = 0; g < ngaps; ++g) (void)hipMemRelease(gaps[g]);   // the memory between the slots goes back
+    std::free(gaps);
+    if (rc != PSGD_OK) {
+        tear_down(s);
+        return rc;
+    }
+    *rec = s;
+    *base_out = s.base;
+    *pitch_out = (int64_t)pitch;
+    return PSGD_OK;
+}
+
+int psgd_spread_free(void* base) {
+    using namespace psgd;
+    clear_error();
+    if (!base) return PSGD_OK;
+    std::lock_guard<std::mutex> lock(g_mu);
+    for (int i = 0; i < kMaxSpreads; ++i)
+        if (g_spreads[i].base == base) {
+            const hipError_t e = hipDeviceSynchronize();              // nothing may still be using the slots
+            tear_down(g_spreads[i]);
+            if (e != hipSuccess) return hip_error(e, "hipDeviceSynchronize");
+            return PSGD_OK;
+        }
+    return fail(PSGD_EINVAL, "psgd_spread_free: %p was not returned by psgd_spread_alloc", base);
+}
+
+}  // extern "C"

@@ -31,6 +31,17 @@ def settled_pool(nbytes, device):
     return torch.empty(nbytes, dtype=torch.uint8, device=device)
 
 
+def settle_allocator(nbytes, device):
+    """Allocate, touch and free `nbytes` in one piece: afterwards the driver hands out physical memory in address
+    order again (see settled_pool), which is what spread_layout() relies on in a process with an allocation
+    history."""
+    pool = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    pool.zero_()
+    torch.cuda.synchronize(device)
+    del pool
+    torch.cuda.empty_cache()
+
+
 def pitched_layout(n, d, specs, span_bytes, device, settle=True):
     """Interleave the rows of several [n, d] arrays in ONE pool so that every array spans
     `span_bytes` of device memory: slot i (at i * pitch) holds row i of each array back to
@@ -52,6 +63,64 @@ def pitched_layout(n, d, specs, span_bytes, device, settle=True):
         flat = pool.view(dt)
         views[name] = flat.as_strided((n, d), (pitch // es, 1), offs[name] // es)
     return views, pool, pitch
+
+
+class SpreadSlots:
+    """Owner of a psgd_spread_alloc allocation: frees it when the last tensor view is gone."""
+
+    def __init__(self, n, slot_bytes, pitch_bytes):
+        self.base, self.pitch = psgd.spread_alloc(n, slot_bytes, pitch_bytes)
+        self.n, self.slot_bytes = n, slot_bytes
+
+    def resident_bytes(self):
+        return self.n * self.slot_bytes
+
+    def close(self):
+        if self.base:
+            base, self.base = self.base, 0
+            psgd.spread_free(base)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class _StridedDeviceArray:
+    """[n, d] rows inside the slots of a SpreadSlots, exposed through the CUDA array interface so that
+    torch.as_tensor() wraps the memory without copying; keeps the owner alive."""
+
+    def __init__(self, owner, offset, n, d, typestr, itemsize):
+        self._owner = owner
+        self.__cuda_array_interface__ = {
+            "shape": (n, d), "typestr": typestr, "data": (owner.base + offset, False), "version": 3,
+            "strides": (owner.pitch, itemsize),
+        }
+
+
+def spread_layout(n, d, specs, span_bytes, device):
+    """The same interleaved layout as pitched_layout() - slot i holds row i of each array back to back, slots
+    `pitch` bytes apart - on memory from psgd_spread_alloc: the slots lie `pitch` apart PHYSICALLY as well, and
+    only the slots are resident (the memory between them has been given back to the driver).  Returns (dict
+    name -> [n, d] strided view, owner, pitch in bytes).  The views keep the owner alive; the memory is not
+    cleared."""
+    def up(v, a):
+        return (v + a - 1) // a * a
+    offs, cur = {}, 0
+    for name, dt in specs:
+        offs[name] = cur
+        cur += up(d * torch.empty((), dtype=dt).element_size(), 4096)
+    pitch = max(cur, (span_bytes // max(n, 1)) // 4096 * 4096)
+    with torch.cuda.device(device):
+        owner = SpreadSlots(n, cur, pitch)
+        views = {}
+        for name, dt in specs:
+            es = torch.empty((), dtype=dt).element_size()
+            typestr = {4: "<f4", 2: "<i2"}[es]
+            t = torch.as_tensor(_StridedDeviceArray(owner, offs[name], n, d, typestr, es), device=device)
+            views[name] = t.view(dt) if t.dtype != dt else t
+    return views, owner, owner.pitch
 
 
 def _window(pool, offset, n, d):

@@ -25,7 +25,7 @@ _lib = None
 EXPORTS = (
     "psgd_build_mixing", "psgd_build_mixing_device", "psgd_mix_step", "psgd_mix_step_bf16g", "psgd_mix_step_cd",
     "psgd_mix_step_cd_bf16g", "psgd_mix_step_ex", "psgd_mix_step_cd_static", "psgd_mix_step_deg", "psgd_mix_full", "psgd_consensus_dist", "psgd_consensus_dist_ex",
-    "psgd_consensus_dist_async", "psgd_synth_grad", "psgd_synth_grad_ex", "psgd_reference_stream", "psgd_device_status", "psgd_last_error",
+    "psgd_consensus_dist_async", "psgd_synth_grad", "psgd_synth_grad_ex", "psgd_reference_stream", "psgd_spread_alloc", "psgd_spread_free", "psgd_device_status", "psgd_last_error",
     "psgd_version",
 )
 
@@ -90,6 +90,11 @@ def load(reload=False):
     lib.psgd_reference_stream.restype = ctypes.c_int
     lib.psgd_reference_stream.argtypes = [ctypes.c_int, vp, ctypes.c_int64, vp, ctypes.c_int64, vp, ctypes.c_int64,
                                           ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_float, vp]
+    lib.psgd_spread_alloc.restype = ctypes.c_int
+    lib.psgd_spread_alloc.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.POINTER(ctypes.c_void_p),
+                                      ctypes.POINTER(ctypes.c_int64)]
+    lib.psgd_spread_free.restype = ctypes.c_int
+    lib.psgd_spread_free.argtypes = [vp]
     lib.psgd_device_status.restype = ctypes.c_int
     lib.psgd_device_status.argtypes = [ctypes.c_int]
     lib.psgd_last_error.restype = ctypes.c_char_p
@@ -350,6 +355,20 @@ def reference_stream(kind, X, X_out, G, a=0.0, stream=None):
     _on_current_device(X, X_out, G)
     _check(load().psgd_reference_stream(int(kind), X.data_ptr(), ldx, X_out.data_ptr(), ldo, G.data_ptr(), ldg, bf16,
                                         n, d, float(a), _stream_handle(stream)))
+
+
+def spread_alloc(n, slot_bytes, pitch_bytes):
+    """n slots of device memory, `pitch` bytes apart in one address range and physically spread out likewise,
+    with only the slots resident (psgd_spread_alloc).  Returns (base address, pitch in bytes); free it with
+    spread_free(base).  Addresses between the slots are not mapped."""
+    base = ctypes.c_void_p()
+    pitch = ctypes.c_int64()
+    _check(load().psgd_spread_alloc(int(n), int(slot_bytes), int(pitch_bytes), ctypes.byref(base), ctypes.byref(pitch)))
+    return base.value, pitch.value
+
+
+def spread_free(base):
+    _check(load().psgd_spread_free(ctypes.c_void_p(base)))
 
 
 def device_status(clear=True):
