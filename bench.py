@@ -161,10 +161,12 @@ def main():
     ap.add_argument("--no-extra-legs", action="store_true",
                     help="skip the measurements that follow the timed region (in-place, dense layout, other workloads, "
                          "reference streams, device copy)")
-    ap.add_argument("--layout", choices=["pitched", "spread", "probe", "dense"], default="pitched",
+    ap.add_argument("--layout", choices=["pitched", "spread", "interleaved", "probe", "dense"], default="pitched",
                     help="where the arrays live in HBM: 'pitched' interleaves the rows of all arrays across most of "
                          "the device (psgd_mix_step_ex), 'spread' is the same layout on psgd_spread_alloc memory "
-                         "(rows physically as far apart, only the rows resident), 'probe' keeps dense arrays but "
+                         "(rows physically as far apart, only the rows resident), 'interleaved' is plain dense arrays in one "
+                         "psgd_interleaved_alloc block (1 GiB pieces from the three thirds of the device's memory in "
+                         "turn), 'probe' keeps dense arrays but "
                          "places X / X_out on the windows of one pool where the step runs fastest, 'dense' is one "
                          "plain tensor per array")
     ap.add_argument("--span-fraction", type=float, default=0.65,
@@ -272,6 +274,21 @@ def main():
             X = inp.fill_normal_rows_(views["X"], wl.sigma_x, wl.seed_x)
             Y = X if args.in_place else views["Y"]
             Gs = [inp.fill_normal_rows_(views["G%d" % i], wl.sigma_g, wl.seed_g + i) for i in range(2)]
+    elif args.layout == "interleaved":
+        specs = [("X", torch.float32)] + ([] if args.in_place else [("Y", torch.float32)])
+        if wl.delay:
+            specs += [("Xprev", torch.float32), ("noise", torch.float32)]
+        specs += [("G0", gdt), ("G1", gdt)]
+        views, pool = plc.interleaved_layout(n, d, specs, dev)
+        data_gb = sum(v.numel() * v.element_size() for v in views.values()) / 1e9
+        layout_report = {"layout": "interleaved", "pool_allocated_GB": (pool.nbytes + (1 << 30) - 1) // (1 << 30) * (1 << 30) / 1e9,
+                         "data_resident_GB": data_gb, "arrays": list(views.keys()),
+                         "note": "dense [n, d] arrays in one psgd_interleaved_alloc block"}
+        log("interleaved layout: dense arrays, %.1f GB allocated for %.1f GB of data"
+            % (layout_report["pool_allocated_GB"], data_gb))
+        X = inp.fill_normal_rows_(views["X"], wl.sigma_x, wl.seed_x)
+        Y = X if args.in_place else views["Y"]
+        Gs = [inp.fill_normal_rows_(views["G%d" % i], wl.sigma_g, wl.seed_g + i) for i in range(2)]
     elif args.layout == "probe":
         # X and X_out are rewritten every step: put them where this chip writes fastest
         Gs = [draw_g(i) for i in range(2)]
@@ -652,28 +669,33 @@ def main():
                                                        ms, layout="pitched", in_place=False, entry_point="psgd_mix_step_ex")
                 del v_, p_
                 torch.cuda.empty_cache()
-        # ---- the headline's workload with only its data resident: rows physically spread by psgd_spread_alloc
-        # instead of living in a pool that spans the device.  In a process of its own: the order in which the
-        # driver hands out physical memory, which that layout relies on, is only in address order in a process
-        # that has not freed large allocations before (64.8-66 % in this process at this point, 76-77.6 % fresh).
+        # ---- the headline's workload with only its data resident, in processes of their own: (i) rows physically
+        # spread by psgd_spread_alloc instead of living in a pool that spans the device, (ii) plain dense arrays in a
+        # psgd_interleaved_alloc block.  Both rely on the order in which the driver hands out physical memory, which
+        # is the address order only in a process that has not freed large allocations before (the spread rows
+        # allocated in this process at this point: 64.8-66 %; fresh: 76-77.6 %).
         torch.cuda.empty_cache()
-        try:
-            child = subprocess.run([sys.executable, os.path.abspath(__file__), "--workload", str(args.workload),
-                                    "--layout", "spread", "--no-extra-legs", "--no-cpu-baseline", "--steps", "5",
-                                    "--warmup", "2", "--span-fraction", str(args.span_fraction)],
-                                   capture_output=True, text=True, timeout=300)
-            r_ = json.loads(child.stdout.strip().splitlines()[-1])
-            roof_, lay_ = r_["roofline"], r_["config"]["hbm_layout"]
-            legs["spread_fresh_process"] = {
-                "workload": wl.name, "avg_launch_ms": roof_["avg_launch_ms"], "value": r_["value"], "unit": "updates/s",
-                "achieved_GBps": roof_["achieved"], "frac": roof_["frac"], "launches": 5, "layout": "spread",
-                "in_place": False, "entry_point": "psgd_mix_step_ex", "allocated_GB": lay_["pool_allocated_GB"],
-                "pitch_GB": lay_["pitch_GB"], "command": "bench.py --layout spread --no-extra-legs --steps 5 --warmup 2"}
-            log("  %-44s %8.3f ms  %7.1f GB/s  %5.1f %% of peak  (%.1f GB allocated)"
-                % ("spread rows, only the data resident", roof_["avg_launch_ms"], roof_["achieved"], 100 * roof_["frac"],
-                   lay_["pool_allocated_GB"]))
-        except Exception as exc:                                      # a leg, not the measurement: report and go on
-            log("  spread leg skipped: %r" % (exc,))
+        for key, lay, label in (("spread_fresh_process", "spread", "spread rows, only the data resident"),
+                                ("dense_interleaved_fresh_process", "interleaved", "dense arrays, interleaved block")):
+            try:
+                child = subprocess.run([sys.executable, os.path.abspath(__file__), "--workload", str(args.workload),
+                                        "--layout", lay, "--no-extra-legs", "--no-cpu-baseline", "--steps", "5",
+                                        "--warmup", "2", "--span-fraction", str(args.span_fraction)],
+                                       capture_output=True, text=True, timeout=300)
+                r_ = json.loads(child.stdout.strip().splitlines()[-1])
+                roof_, lay_ = r_["roofline"], r_["config"]["hbm_layout"]
+                legs[key] = {
+                    "workload": wl.name, "avg_launch_ms": roof_["avg_launch_ms"], "value": r_["value"], "unit": "updates/s",
+                    "achieved_GBps": roof_["achieved"], "frac": roof_["frac"], "launches": 5, "layout": lay,
+                    "in_place": False,
+                    "entry_point": "psgd_mix_step_ex" if lay == "spread" else
+                                   ("psgd_mix_step_cd_bf16g" if wl.g_dtype == "bf16" else "psgd_mix_step_cd"),
+                    "allocated_GB": lay_["pool_allocated_GB"],
+                    "command": "bench.py --layout %s --no-extra-legs --steps 5 --warmup 2" % lay}
+                log("  %-44s %8.3f ms  %7.1f GB/s  %5.1f %% of peak  (%.1f GB allocated)"
+                    % (label, roof_["avg_launch_ms"], roof_["achieved"], 100 * roof_["frac"], lay_["pool_allocated_GB"]))
+            except Exception as exc:                                  # a leg, not the measurement: report and go on
+                log("  %s leg skipped: %r" % (lay, exc))
         result["legs"] = legs
         if psgd.device_status() != 0:
             log("bench.py: a kernel flagged an invalid mixing table")

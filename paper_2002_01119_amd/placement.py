@@ -123,6 +123,54 @@ def spread_layout(n, d, specs, span_bytes, device):
     return views, owner, owner.pitch
 
 
+class InterleavedBlock:
+    """Owner of a psgd_interleaved_alloc block: frees it when the last tensor view is gone."""
+
+    def __init__(self, nbytes):
+        self.base = psgd.interleaved_alloc(nbytes)
+        self.pitch = 0                       # unused: the arrays carved from the block are dense
+        self.nbytes = nbytes
+
+    def close(self):
+        if self.base:
+            base, self.base = self.base, 0
+            psgd.interleaved_free(base)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class _DenseDeviceArray:
+    def __init__(self, owner, offset, shape, typestr):
+        self._owner = owner
+        self.__cuda_array_interface__ = {"shape": tuple(shape), "typestr": typestr, "data": (owner.base + offset, False),
+                                         "version": 3, "strides": None}
+
+
+def interleaved_layout(n, d, specs, device):
+    """Plain dense [n, d] arrays, one per (name, torch dtype) in `specs`, back to back (4 KB aligned) in ONE block
+    from psgd_interleaved_alloc: wherever an array starts, its rows are spread evenly over the three thirds of
+    the device's physical memory.  Call it before anything else allocates much (see psgd.h).  Returns (dict name
+    -> [n, d] contiguous tensor, owner).  The tensors keep the owner alive; the memory is not cleared."""
+    def up(v, a):
+        return (v + a - 1) // a * a
+    offs, cur = {}, 0
+    for name, dt in specs:
+        offs[name] = cur
+        cur += up(n * d * torch.empty((), dtype=dt).element_size(), 4096)
+    with torch.cuda.device(device):
+        owner = InterleavedBlock(cur)
+        views = {}
+        for name, dt in specs:
+            es = torch.empty((), dtype=dt).element_size()
+            t = torch.as_tensor(_DenseDeviceArray(owner, offs[name], (n, d), {4: "<f4", 2: "<i2"}[es]), device=device)
+            views[name] = t.view(dt) if t.dtype != dt else t
+    return views, owner
+
+
 def _window(pool, offset, n, d):
     return pool[offset:offset + n * d * 4].view(torch.float32).view(n, d)
 

@@ -25,7 +25,7 @@ _lib = None
 EXPORTS = (
     "psgd_build_mixing", "psgd_build_mixing_device", "psgd_mix_step", "psgd_mix_step_bf16g", "psgd_mix_step_cd",
     "psgd_mix_step_cd_bf16g", "psgd_mix_step_ex", "psgd_mix_step_cd_static", "psgd_mix_step_deg", "psgd_mix_full", "psgd_consensus_dist", "psgd_consensus_dist_ex",
-    "psgd_consensus_dist_async", "psgd_synth_grad", "psgd_synth_grad_ex", "psgd_reference_stream", "psgd_spread_alloc", "psgd_spread_free", "psgd_device_status", "psgd_last_error",
+    "psgd_consensus_dist_async", "psgd_synth_grad", "psgd_synth_grad_ex", "psgd_reference_stream", "psgd_spread_alloc", "psgd_spread_free", "psgd_interleaved_alloc", "psgd_interleaved_free", "psgd_device_status", "psgd_last_error",
     "psgd_version",
 )
 
@@ -95,6 +95,10 @@ def load(reload=False):
                                       ctypes.POINTER(ctypes.c_int64)]
     lib.psgd_spread_free.restype = ctypes.c_int
     lib.psgd_spread_free.argtypes = [vp]
+    lib.psgd_interleaved_alloc.restype = ctypes.c_int
+    lib.psgd_interleaved_alloc.argtypes = [ctypes.c_int64, ctypes.POINTER(ctypes.c_void_p)]
+    lib.psgd_interleaved_free.restype = ctypes.c_int
+    lib.psgd_interleaved_free.argtypes = [vp]
     lib.psgd_device_status.restype = ctypes.c_int
     lib.psgd_device_status.argtypes = [ctypes.c_int]
     lib.psgd_last_error.restype = ctypes.c_char_p
@@ -369,6 +373,19 @@ def spread_alloc(n, slot_bytes, pitch_bytes):
 
 def spread_free(base):
     _check(load().psgd_spread_free(ctypes.c_void_p(base)))
+
+
+def interleaved_alloc(nbytes):
+    """One block of device memory at consecutive addresses whose 1 GiB pieces come from the three thirds of the
+    device's physical memory in turn (psgd_interleaved_alloc).  Returns its address; free it with
+    interleaved_free()."""
+    ptr = ctypes.c_void_p()
+    _check(load().psgd_interleaved_alloc(int(nbytes), ctypes.byref(ptr)))
+    return ptr.value
+
+
+def interleaved_free(ptr):
+    _check(load().psgd_interleaved_free(ctypes.c_void_p(ptr)))
 
 
 def device_status(clear=True):

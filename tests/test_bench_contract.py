@@ -60,6 +60,7 @@ def test_json_line_on_the_small_workload():
     ["--workload", "2", "--two-rings"],
     ["--workload", "2", "--g-apart"],
     ["--workload", "2", "--layout", "spread"],
+    ["--workload", "2", "--layout", "interleaved"],
 ])
 def test_variants_run_and_report(flags):
     """Every benchmark variant runs to completion and prints one well-formed line."""
@@ -87,7 +88,8 @@ def test_default_form_reports_the_legs_it_is_read_against():
     assert p.returncode == 0, p.stderr[-2000:]
     r = json.loads(p.stdout.strip())
     for key in ("pitched_out_of_place", "pitched_in_place", "dense_out_of_place", "dense_in_place",
-                "tiled_two_rings_pitched", "tiled_degree13_pitched", "consensus_alone_pitched", "spread_fresh_process"):
+                "tiled_two_rings_pitched", "tiled_degree13_pitched", "consensus_alone_pitched", "spread_fresh_process",
+                "dense_interleaved_fresh_process"):
         leg = r["legs"][key]
         assert 0.2 < leg["frac"] < 1.0 and leg["avg_launch_ms"] > 0 and leg["workload"].startswith("cfg2"), (key, leg)
     for block in ("reference_streams", "reference_streams_dense"):

@@ -1,6 +1,6 @@
-"""psgd_spread_alloc / psgd_spread_free (placement support): the slots are usable device memory at the promised
-addresses, only the slots stay allocated, the step runs on views of them and matches the oracle, and bad
-arguments are refused."""
+"""psgd_spread_alloc and psgd_interleaved_alloc (placement support): the memory is usable at the promised
+addresses, only what was asked for stays allocated, the step runs on views of it and matches the oracle, and
+bad arguments are refused."""
 import ctypes
 
 import numpy as np
@@ -85,3 +85,58 @@ def test_bad_arguments_are_refused(psgd):
     psgd.spread_free(b)
     with pytest.raises(psgd.PsgdError):
         psgd.spread_free(b)
+
+
+def test_step_on_dense_arrays_in_an_interleaved_block_matches_the_oracle(psgd):
+    dev = torch.device("cuda:0")
+    n, d = 10, 30_000_004                                   # X and Y 1.2 GB each, G 0.6 GB: the block spans 3 GiB pieces
+    specs = [("X", torch.float32), ("Y", torch.float32), ("G", torch.bfloat16)]
+    torch.cuda.empty_cache()
+    free0 = torch.cuda.mem_get_info()[0]
+    views, owner = plc.interleaved_layout(n, d, specs, dev)
+    used = free0 - torch.cuda.mem_get_info()[0]
+    assert (3 << 30) - (64 << 20) <= used <= (3 << 30) + (256 << 20), used    # three 1 GiB pieces, and nothing else kept
+    for name, dt in specs:
+        v = views[name]
+        assert v.shape == (n, d) and v.dtype == dt and v.is_contiguous() and v.data_ptr() % 4096 == 0
+    assert views["X"].data_ptr() == owner.base and views["Y"].data_ptr() > views["X"].data_ptr()
+    X = inp.fill_normal_rows_(views["X"], 1.0, 21)
+    G = inp.fill_normal_rows_(views["G"], 0.1, 22)
+    Y = views["Y"]
+    Y.fill_(float("nan"))
+    nbr, w = psgd.build_mixing(psgd.TOPO_RAND_RING, n, 6, 1)
+    cd = torch.zeros(1, dtype=torch.float64, device=dev)
+    psgd.mix_step(X, Y, G, torch.from_numpy(nbr).to(dev), torch.from_numpy(w).to(dev), 0.1, cdist_out=cd)
+    torch.cuda.synchronize()
+    assert psgd.device_status() == 0
+    T = orc.densify(nbr, w)
+    c_sum = 0.0
+    for lo in range(0, d, 6_000_000):                       # column blocks: the oracle works in fp64
+        hi = min(lo + 6_000_000, d)
+        Xh, Gh = X[:, lo:hi].contiguous().cpu().numpy(), inp.bf16_tensor_bits(G[:, lo:hi])
+        Yh = Y[:, lo:hi].contiguous().cpu().numpy()
+        want = orc.mix_step(Xh, Gh, T, 0.1)
+        assert np.abs(Yh - want).max() <= REL * np.abs(want).max(), lo
+        c_sum += orc.consensus_dist(Yh)
+    assert abs(cd.item() - c_sum) <= REL * c_sum
+    del views, X, Y, G, v
+    torch.cuda.empty_cache()
+    free1 = torch.cuda.mem_get_info()[0]
+    owner.close()
+    assert torch.cuda.mem_get_info()[0] - free1 >= (3 << 30) - (64 << 20)
+    owner.close()
+
+
+def test_interleaved_bad_arguments_are_refused(psgd):
+    lib = psgd.load()
+    ptr = ctypes.c_void_p()
+    assert lib.psgd_interleaved_alloc(0, ctypes.byref(ptr)) == psgd.EINVAL and ptr.value is None
+    assert lib.psgd_interleaved_alloc(-5, ctypes.byref(ptr)) == psgd.EINVAL
+    assert lib.psgd_interleaved_alloc(4096, None) == psgd.EINVAL
+    assert lib.psgd_interleaved_alloc(1 << 50, ctypes.byref(ptr)) == psgd.EHIP and "fit" in psgd.last_error()
+    assert lib.psgd_interleaved_free(None) == psgd.OK
+    assert lib.psgd_interleaved_free(ctypes.c_void_p(0x2000)) == psgd.EINVAL
+    p = psgd.interleaved_alloc(100)                          # rounded up to one piece
+    psgd.interleaved_free(p)
+    with pytest.raises(psgd.PsgdError):
+        psgd.interleaved_free(p)
