@@ -90,6 +90,6 @@ int psgd_build_mixing(int topology, int n, uint64_t seed, uint64_t step, int32_t
 
 const char* psgd_last_error(void) { return psgd::g_err; }
 
-int psgd_version(void) { return 2; }
+int psgd_version(void) { return 3; }
 
 }  // extern "C"
