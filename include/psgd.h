@@ -324,9 +324,11 @@ int psgd_spread_free(void* base);
  * (psgd_mix_step, psgd_mix_step_cd_bf16g, ...) run at the rate of the spread rows (77 % of the HBM peak for
  * the step on 64 x 1e8 elements, against 59-76 % on ordinary allocations).
  *
- * While the call runs it holds all free device memory but 4 GiB (that is how it reaches the thirds), so the
- * block is best allocated first, in a process that has not freed large allocations before: the position of a
- * piece is inferred from the order in which the driver hands memory out.  Where that order does not hold the
+ * While the call runs it holds all free device memory but 4 GiB (that is how it reaches every third) and
+ * measures which third each 1 GiB piece lies in: two pieces written together by a small kernel on the null
+ * stream take a quarter longer when they share a third.  The call therefore takes a few seconds (4 s with
+ * 280 GiB free), synchronises with the device, and must not run under stream capture.  Being measured, the
+ * placement does not depend on what the process allocated and freed before.  Where the measurement shows no such structure the
  * block is still valid memory, only not faster than any other.  The memory is not cleared.  At most 16 blocks
  * live at a time; psgd_interleaved_free(ptr) waits for the device and releases the block.
  * Errors: PSGD_EINVAL (arguments, unknown pointer), PSGD_EHIP (does not fit, or the runtime refused; nothing

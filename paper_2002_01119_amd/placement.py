@@ -15,8 +15,9 @@ the library's own kernels):
   place_replica_buffers dense arrays on the fastest windows of a probed pool (the step itself, in place, is timed
                         on candidate windows)
 
-spread_layout and interleaved_layout infer physical positions from the order in which the driver hands out
-memory, which is the address order in a process that has not freed large allocations before: call them first.
+spread_layout infers physical positions from the order in which the driver hands out memory, which is the
+address order in a process that has not freed large allocations before: call it first.  interleaved_layout
+measures them (a few seconds) and does not care.
 """
 import torch
 
@@ -159,7 +160,8 @@ class _DenseDeviceArray:
 def interleaved_layout(n, d, specs, device):
     """Plain dense [n, d] arrays, one per (name, torch dtype) in `specs`, back to back (4 KB aligned) in ONE block
     from psgd_interleaved_alloc: wherever an array starts, its rows are spread evenly over the three thirds of
-    the device's physical memory.  Call it before anything else allocates much (see psgd.h).  Returns (dict name
+    the device's physical memory (measured by the call: it takes a few seconds and needs the device's free memory
+    for that long).  Returns (dict name
     -> [n, d] contiguous tensor, owner).  The tensors keep the owner alive; the memory is not cleared."""
     def up(v, a):
         return (v + a - 1) // a * a
