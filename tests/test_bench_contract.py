@@ -57,8 +57,6 @@ def test_json_line_on_the_small_workload():
     ["--workload", "2", "--degree", "5"],
     ["--workload", "4", "--overlap"],
     ["--workload", "4", "--graph", "--no-consensus"],
-    ["--workload", "2", "--two-rings"],
-    ["--workload", "2", "--g-apart"],
     ["--workload", "2", "--layout", "spread"],
     ["--workload", "2", "--layout", "interleaved"],
 ])

@@ -7,6 +7,7 @@ Gaussian inputs (covariance propagation of Sec. 3's argument, exact up to O(1/sq
 sampling noise) and, on a structured array, against a closed form that is exact at any size.
 """
 import math
+import os
 
 import numpy as np
 import pytest
@@ -337,20 +338,32 @@ def _every_element_one_step(psgd, wl, step_index):
     max_err = max_out = 0.0
     err2 = out2 = 0.0
     c_sum = 0.0
-    for lo in range(0, d, block):
+    threads = min(16, os.cpu_count() or 1)
+    for bi, lo in enumerate(range(0, d, block)):
         hi = min(lo + block, d)
         Xb = X[:, lo:hi].contiguous().cpu().numpy()
         Gb = inp.bf16_tensor_bits(G[:, lo:hi]) if wl.g_dtype == "bf16" else G[:, lo:hi].contiguous().cpu().numpy()
         Yb = Y[:, lo:hi].contiguous().cpu().numpy()
-        want = orc.mix_step(Xb, Gb, T, wl.lr)
+        # every block against the oracle's sparse form (the same definition as a gather-add in C, pinned against the
+        # dense product on the CPU); the first, the last and every sixth block also against the dense product itself
+        want = orc.sparse_mix_step(Xb, Gb, nbr, w, wl.lr, threads=threads)
+        if bi % 6 == 0 or hi == d:
+            dense = orc.mix_step(Xb, Gb, T, wl.lr)
+            assert np.abs(dense - want).max() <= 1e-12 * max(np.abs(dense).max(), 1e-30)
         diff = Yb - want                                   # fp32 - fp64 -> fp64; NaN if an output was never written
-        e = float(np.abs(diff).max())
+        e = max(float(diff.max()), -float(diff.min()))     # NaN propagates through max and min
         assert e == e, "unwritten output in columns %d..%d" % (lo, hi)
         max_err = max(max_err, e)
-        max_out = max(max_out, float(np.abs(want).max()))
-        err2 += float((diff * diff).sum())
-        out2 += float((want * want).sum())
-        c_sum += orc.consensus_dist(Yb)                    # columns are independent: the distance adds up
+        max_out = max(max_out, float(want.max()), -float(want.min()))
+        dv, wv = diff.reshape(-1), want.reshape(-1)
+        err2 += float(np.dot(dv, dv))
+        out2 += float(np.dot(wv, wv))
+        if bi % 6 == 0 or hi == d:                         # columns are independent: the distance adds up
+            c_blk = orc.consensus_dist(Yb)
+            assert abs(orc.sparse_consensus_dist(Yb, threads=threads) - c_blk) <= 1e-12 * c_blk
+        else:
+            c_blk = orc.sparse_consensus_dist(Yb, threads=threads)
+        c_sum += c_blk
         # every block by itself already meets the bar against the magnitudes seen so far
         assert max_err <= REL * max_out, "columns %d..%d: err %.3g vs %.3g" % (lo, hi, max_err, max_out)
     assert max_err <= REL * max_out
